@@ -1,0 +1,168 @@
+/*
+ * smoe.h -- C ABI of libsmoe: ScatterMoE's ParallelLinear hot path on AMD MI355X (gfx950).
+ *
+ * The operations are the ones the paper "Scattered Mixture-of-Experts Implementation"
+ * (arXiv 2403.08245) defines: routing indices (Sec. 3.1 steps 1-2), ParallelLinear
+ * forward (Alg. 1) and backward (Alg. 2, Sec. 3.2.1), and the SMoE MLP built from two
+ * ParallelLinears (Alg. 3).  Notation follows the paper: T tokens, E experts, top-k,
+ * Tk = T*k routed slots, slot s = t*k + j.
+ *
+ * General conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller, on the device the
+ *     context was created for.  Tensors are contiguous, row-major.  Index arrays are
+ *     int32.  The library never frees or keeps a caller buffer past the call's work.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued on it; no entry point synchronises, allocates device memory or copies to
+ *     the host.  Results are ready when the stream reaches the end of the enqueued work.
+ *   - `ws` / `ws_bytes`: scratch device memory supplied by the caller, at least as large
+ *     as the matching *_workspace_bytes() query, 256-byte aligned.  Contents are
+ *     unspecified on entry and on return.
+ *   - Return value: SMOE_OK (0) or a negative smoe_status.  On error nothing has been
+ *     enqueued.  No entry point throws or aborts.  Index *contents* (expert ids in
+ *     [0,E), a valid permutation in sorted_scattered_idxs) are the caller's contract:
+ *     they live on the device and are not validated; out-of-range expert ids passed to
+ *     smoe_route are clamped so that no out-of-bounds access happens.
+ *   - Outputs are overwritten, never accumulated into.  All kernels are deterministic
+ *     (no floating-point atomics): two identical calls give bit-identical results.
+ *   - dtype: SMOE_F32 computes with fp32 FMA accumulation; SMOE_BF16 takes bf16 inputs,
+ *     accumulates in fp32 on the matrix cores and rounds each stored tensor to bf16
+ *     (round-to-nearest-even).  gates and dgates are always fp32.
+ */
+#ifndef SMOE_H_
+#define SMOE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct smoe_ctx smoe_ctx; /* opaque; holds the device id and launch heuristics */
+
+typedef enum { SMOE_F32 = 0, SMOE_BF16 = 1 } smoe_dtype;
+
+/* Alg. 3's point-wise non-linearity.  GELU is the exact erf form.  SWIGLU reads a
+ * [.., 2*d_expert] pre-activation packed as [gate | up] and yields silu(gate) * up. */
+typedef enum { SMOE_ACT_NONE = 0, SMOE_ACT_GELU = 1, SMOE_ACT_SWIGLU = 2 } smoe_act;
+
+typedef enum {
+  SMOE_OK = 0,
+  SMOE_ERR_INVALID_ARG = -1,   /* null pointer, non-positive size, inconsistent flags   */
+  SMOE_ERR_UNSUPPORTED = -2,   /* valid request this build has no kernel for            */
+  SMOE_ERR_WORKSPACE = -3,     /* ws is NULL / misaligned / smaller than required       */
+  SMOE_ERR_HIP = -4            /* a HIP runtime call (launch, device query) failed      */
+} smoe_status;
+
+/* The routing products of Sec. 3.1 step 2 ("sort the tokens according to the experts").
+ * sorted_scattered_idxs is the paper's order-index vector o (Alg. 1-3): entry i is the
+ * slot id t*k+j of the i-th row in expert-sorted order; inside an expert slots ascend. */
+typedef struct {
+  const int32_t *sorted_expert_idxs;    /* [Tk] expert of the i-th sorted row, non-decreasing   */
+  const int32_t *sorted_scattered_idxs; /* [Tk] permutation of 0..Tk-1 (o)                      */
+  const int32_t *expert_offsets;        /* [E+1] exclusive prefix sums of per-expert row counts */
+  int32_t Tk;
+  int32_t E;
+} smoe_routing;
+
+/* Creates a context for HIP device `device` (host call; queries device properties).
+ * *out is owned by the caller until smoe_destroy.  One context may be used from several
+ * streams; it holds no mutable state on the hot path. */
+int smoe_create(smoe_ctx **out, int device);
+void smoe_destroy(smoe_ctx *ctx);
+/* Static string for a smoe_status value. */
+const char *smoe_strerror(int status);
+/* ABI version, bumped when a signature changes. */
+int smoe_abi_version(void);
+
+/* Selects the GEMM kernel family: 0 = automatic (matrix-core kernels whenever the shape
+ * allows), 1 = force the plain tiled kernels (testing aid).  Host-only, not thread safe. */
+int smoe_set_kernel_mode(smoe_ctx *ctx, int mode);
+
+/* ---- routing: Sec. 3.1 step 1 -------------------------------------------------------
+ * For each token keeps the k largest of its E router logits (ties to the lower expert
+ * id, slots ordered by descending logit) and the softmax over those k logits.
+ *   logits      [T,E] fp32 (in)
+ *   expert_idxs [T*k] int32 (out), gates [T*k] fp32 (out), both in slot order t*k+j.
+ * Needs 1 <= k <= E.  T = 0 is a no-op. */
+int smoe_topk_gate(smoe_ctx *ctx, void *stream, const float *logits, int T, int E, int k,
+                   int32_t *expert_idxs, float *gates);
+
+/* ---- routing: Sec. 3.1 step 2 -------------------------------------------------------
+ * Stable bucket sort of the Tk = T*k slots by expert.  Outputs as in smoe_routing.
+ * Integer work, bit-exact.  Experts nobody chose get an empty segment. */
+size_t smoe_route_workspace_bytes(int T, int k, int E);
+int smoe_route(smoe_ctx *ctx, void *stream, const int32_t *expert_idxs, int T, int k, int E,
+               int32_t *sorted_expert_idxs, int32_t *sorted_scattered_idxs,
+               int32_t *expert_offsets, void *ws, size_t ws_bytes);
+
+/* ---- ParallelLinear forward: Alg. 1 (scatter2scatter, Sec. 3.2, Fig. 2) --------------
+ *   X     [x_rows, d_in]  grouped_in = 0: scattered, the row of slot s is s / k (fan-out k,
+ *                         so x_rows = Tk / k); grouped_in = 1: expert-sorted, x_rows = Tk, k = 1.
+ *   W     [E, d_in, d_out]
+ *   Yhat  [Tk, d_out] (out) row i (grouped_out = 1) or row o[i] (grouped_out = 0) is the
+ *                         i-th sorted input row times its expert's matrix.
+ *   gates optional [Tk] fp32 in slot order viewed as [T, kp] with kp = gates_k; when given,
+ *         grouped_out must be 0 and Y [Tk / gates_k, d_out] (out) receives
+ *         Y[t] = sum_j gates[t*kp+j] * Yhat[t*kp+j]   (Alg. 1's view + bmm).
+ *         gates = NULL: Y must be NULL and Yhat is the result.
+ * No workspace is needed. */
+int smoe_plinear_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *X, int x_rows,
+                     int d_in, const void *W, int d_out, const smoe_routing *r, int k,
+                     const float *gates, int gates_k, int grouped_in, int grouped_out,
+                     void *Yhat, void *Y);
+
+/* ---- ParallelLinear backward: Alg. 2, Sec. 3.2.1 -------------------------------------
+ * Gradients of Alg. 1's result.  dY has the shape of Alg. 1's output: [Tk/gates_k, d_out]
+ * when gates were given, else [Tk, d_out] in the order grouped_out says.
+ *   Yhat   forward's unweighted [Tk, d_out] (scattered); read only when gates != NULL.
+ *   dX     (out) same shape as X; with scattered input the k slot gradients of a row are summed.
+ *   dW     (out) [E, d_in, d_out] in the weight dtype; zeros for experts with no rows.
+ *   dgates (out, nullable) [Tk] fp32, dgates[s] = <dY[s / gates_k], Yhat[s]>.
+ * Either of dX / dW may be NULL to skip it.  Steps: weighted group of dY (only when it is
+ * scattered), groupXTY for dW, scatter2scatter with W^T for dX. */
+size_t smoe_plinear_bwd_workspace_bytes(smoe_dtype dtype, int x_rows, int d_in, int d_out, int Tk,
+                                        int k, int has_gates, int grouped_in, int grouped_out);
+int smoe_plinear_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *dY, const void *X,
+                     int x_rows, int d_in, const void *W, int d_out, const void *Yhat,
+                     const smoe_routing *r, int k, const float *gates, int gates_k, int grouped_in,
+                     int grouped_out, void *dX, void *dW, float *dgates, void *ws, size_t ws_bytes);
+
+/* ---- SMoE MLP: Alg. 3 -----------------------------------------------------------------
+ * Y[t] = sum_j gates[t*k+j] * act(X[t] W1[e]) W2[e]  over the token's k experts (Sec. 3.1
+ * step 5), computed as ParallelLinear(scattered->grouped), act, ParallelLinear(grouped->
+ * scattered, weighted).
+ *   X [T, d_model];  W1 [E, d_model, d_h] with d_h = 2*d_expert for SWIGLU else d_expert;
+ *   W2 [E, d_expert, d_model];  gates [T*k] fp32;  Y [T, d_model] (out).
+ *   saved_Hpre [Tk, d_h], saved_H [Tk, d_expert] (expert-sorted order) and saved_Yhat
+ *   [Tk, d_model] (slot order): outputs kept for the backward pass.  Pass all three or
+ *   none; with none (inference) the workspace holds them instead. */
+size_t smoe_mlp_fwd_workspace_bytes(smoe_dtype dtype, smoe_act act, int T, int k, int d_model,
+                                    int d_expert, int training);
+int smoe_mlp_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, const void *X, int T,
+                 int d_model, int d_expert, const void *W1, const void *W2, const smoe_routing *r,
+                 int k, const float *gates, void *Y, void *saved_Hpre, void *saved_H,
+                 void *saved_Yhat, void *ws, size_t ws_bytes);
+
+/* Backward of smoe_mlp_fwd (Alg. 2 applied to both ParallelLinears, one `group` each).
+ *   dY [T, d_model] upstream gradient; saved_* from the forward call.
+ *   dX [T, d_model], dW1 like W1, dW2 like W2, dgates [T*k] fp32 (all out, none nullable). */
+size_t smoe_mlp_bwd_workspace_bytes(smoe_dtype dtype, smoe_act act, int T, int k, int d_model,
+                                    int d_expert);
+int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, const void *dY,
+                 const void *X, int T, int d_model, int d_expert, const void *W1, const void *W2,
+                 const smoe_routing *r, int k, const float *gates, const void *saved_Hpre,
+                 const void *saved_H, const void *saved_Yhat, void *dX, void *dW1, void *dW2,
+                 float *dgates, void *ws, size_t ws_bytes);
+
+/* ---- the `group` copy of Alg. 2 --------------------------------------------------------
+ * out[i] = scale_i * in[o[i] / fan] for the Tk sorted rows, scale_i = gates[o[i]] or 1 when
+ * gates is NULL.  in [Tk/fan, d], out [Tk, d].  Exposed because Alg. 2 names it; the
+ * forward path never needs it. */
+int smoe_group(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *in, int d,
+               const smoe_routing *r, int fan, const float *gates, void *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SMOE_H_ */

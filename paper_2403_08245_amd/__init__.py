@@ -1,0 +1,262 @@
+"""Python binding of libsmoe (ScatterMoE's ParallelLinear hot path on MI355X).
+
+Argument marshalling only: every function here checks tensor dtypes/contiguity, allocates
+outputs and scratch with torch, and calls the C entry point of the same name
+(smoe_<name>, declared in include/smoe.h) on torch's current HIP stream.  There is no
+Python or PyTorch fallback: if libsmoe.so is missing, importing this package fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+ACT_NONE, ACT_GELU, ACT_SWIGLU = 0, 1, 2
+F32, BF16 = 0, 1
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libsmoe.so")
+
+EXPORTS = [
+    "smoe_create", "smoe_destroy", "smoe_strerror", "smoe_abi_version", "smoe_set_kernel_mode",
+    "smoe_topk_gate", "smoe_route_workspace_bytes", "smoe_route",
+    "smoe_plinear_fwd", "smoe_plinear_bwd_workspace_bytes", "smoe_plinear_bwd",
+    "smoe_mlp_fwd_workspace_bytes", "smoe_mlp_fwd", "smoe_mlp_bwd_workspace_bytes", "smoe_mlp_bwd",
+    "smoe_group",
+]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} not found: build it first (python -m paper_2403_08245_amd.build); "
+            "this package has no fallback path")
+    return ctypes.CDLL(LIB_PATH)
+
+
+lib = _load()
+
+_vp, _i, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+
+
+class smoe_routing(ctypes.Structure):
+    _fields_ = [("sorted_expert_idxs", _vp), ("sorted_scattered_idxs", _vp), ("expert_offsets", _vp),
+                ("Tk", ctypes.c_int32), ("E", ctypes.c_int32)]
+
+
+_rp = ctypes.POINTER(smoe_routing)
+lib.smoe_create.argtypes = [ctypes.POINTER(_vp), _i]
+lib.smoe_destroy.argtypes = [_vp]
+lib.smoe_destroy.restype = None
+lib.smoe_strerror.argtypes = [_i]
+lib.smoe_strerror.restype = ctypes.c_char_p
+lib.smoe_set_kernel_mode.argtypes = [_vp, _i]
+lib.smoe_topk_gate.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp, _vp]
+lib.smoe_route_workspace_bytes.argtypes = [_i, _i, _i]
+lib.smoe_route_workspace_bytes.restype = _sz
+lib.smoe_route.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _sz]
+lib.smoe_plinear_fwd.argtypes = [_vp, _vp, _i, _vp, _i, _i, _vp, _i, _rp, _i, _vp, _i, _i, _i, _vp, _vp]
+lib.smoe_plinear_bwd_workspace_bytes.argtypes = [_i] * 9
+lib.smoe_plinear_bwd_workspace_bytes.restype = _sz
+lib.smoe_plinear_bwd.argtypes = [_vp, _vp, _i, _vp, _vp, _i, _i, _vp, _i, _vp, _rp, _i, _vp, _i, _i, _i,
+                                 _vp, _vp, _vp, _vp, _sz]
+lib.smoe_mlp_fwd_workspace_bytes.argtypes = [_i] * 7
+lib.smoe_mlp_fwd_workspace_bytes.restype = _sz
+lib.smoe_mlp_fwd.argtypes = [_vp, _vp, _i, _i, _vp, _i, _i, _i, _vp, _vp, _rp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _sz]
+lib.smoe_mlp_bwd_workspace_bytes.argtypes = [_i] * 6
+lib.smoe_mlp_bwd_workspace_bytes.restype = _sz
+lib.smoe_mlp_bwd.argtypes = [_vp, _vp, _i, _i, _vp, _vp, _i, _i, _i, _vp, _vp, _rp, _i, _vp, _vp, _vp, _vp,
+                             _vp, _vp, _vp, _vp, _vp, _sz]
+lib.smoe_group.argtypes = [_vp, _vp, _i, _vp, _i, _rp, _i, _vp, _vp]
+
+
+class SmoeError(RuntimeError):
+    pass
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise SmoeError(f"{what}: {lib.smoe_strerror(rc).decode()} ({rc})")
+
+
+_ctx_by_device: dict[int, ctypes.c_void_p] = {}
+
+
+def ctx(device: int | None = None) -> ctypes.c_void_p:
+    """The library context of a device (created on first use)."""
+    dev = torch.cuda.current_device() if device is None else device
+    if dev not in _ctx_by_device:
+        h = _vp()
+        _check(lib.smoe_create(ctypes.byref(h), dev), "smoe_create")
+        _ctx_by_device[dev] = h
+    return _ctx_by_device[dev]
+
+
+def set_kernel_mode(mode: int):
+    _check(lib.smoe_set_kernel_mode(ctx(), mode), "smoe_set_kernel_mode")
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _p(t):
+    return None if t is None else t.data_ptr()
+
+
+def _chk(t: torch.Tensor, dtype=None):
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors must be contiguous device tensors")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {t.dtype}")
+    return t
+
+
+def _ws(nbytes: int, device) -> torch.Tensor | None:
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+@dataclass
+class Routing:
+    """Device arrays of Sec. 3.1 step 2 plus the ctypes view the C ABI takes."""
+    sorted_expert_idxs: torch.Tensor
+    sorted_scattered_idxs: torch.Tensor
+    expert_offsets: torch.Tensor
+    Tk: int
+    E: int
+
+    def c(self) -> smoe_routing:
+        return smoe_routing(self.sorted_expert_idxs.data_ptr(), self.sorted_scattered_idxs.data_ptr(),
+                            self.expert_offsets.data_ptr(), self.Tk, self.E)
+
+
+def topk_gate(logits: torch.Tensor, k: int):
+    _chk(logits, torch.float32)
+    T, E = logits.shape
+    idx = torch.empty(T, k, dtype=torch.int32, device=logits.device)
+    gates = torch.empty(T, k, dtype=torch.float32, device=logits.device)
+    _check(lib.smoe_topk_gate(ctx(), _stream(), _p(logits), T, E, k, _p(idx), _p(gates)), "smoe_topk_gate")
+    return idx, gates
+
+
+def route(expert_idxs: torch.Tensor, E: int) -> Routing:
+    _chk(expert_idxs, torch.int32)
+    T, k = expert_idxs.shape
+    dev = expert_idxs.device
+    se = torch.empty(T * k, dtype=torch.int32, device=dev)
+    so = torch.empty(T * k, dtype=torch.int32, device=dev)
+    off = torch.empty(E + 1, dtype=torch.int32, device=dev)
+    nb = lib.smoe_route_workspace_bytes(T, k, E)
+    ws = _ws(nb, dev)
+    _check(lib.smoe_route(ctx(), _stream(), _p(expert_idxs), T, k, E, _p(se), _p(so), _p(off), _p(ws), ws.numel()),
+           "smoe_route")
+    return Routing(se, so, off, T * k, E)
+
+
+def group(x: torch.Tensor, r: Routing, fan: int, gates: torch.Tensor | None = None) -> torch.Tensor:
+    _chk(x)
+    out = torch.empty(r.Tk, x.shape[1], dtype=x.dtype, device=x.device)
+    rc = r.c()
+    _check(lib.smoe_group(ctx(), _stream(), _dt(x), _p(x), x.shape[1], ctypes.byref(rc), fan,
+                          _p(None if gates is None else _chk(gates, torch.float32)), _p(out)), "smoe_group")
+    return out
+
+
+def plinear_fwd(X, W, r: Routing, k: int, gates=None, grouped_in=False, grouped_out=False):
+    """Alg. 1.  Returns (Y, Yhat); Y is Yhat when no gates are given."""
+    _chk(X); _chk(W, X.dtype)
+    d_in, d_out = W.shape[1], W.shape[2]
+    Yhat = torch.empty(r.Tk, d_out, dtype=X.dtype, device=X.device)
+    Y, gk = None, 0
+    if gates is not None:
+        _chk(gates, torch.float32)
+        gk = gates.shape[1]
+        Y = torch.empty(r.Tk // gk, d_out, dtype=X.dtype, device=X.device)
+    rc = r.c()
+    _check(lib.smoe_plinear_fwd(ctx(), _stream(), _dt(X), _p(X), X.shape[0], d_in, _p(W), d_out, ctypes.byref(rc), k,
+                                _p(gates), gk, int(grouped_in), int(grouped_out), _p(Yhat), _p(Y)), "smoe_plinear_fwd")
+    return (Yhat if Y is None else Y), Yhat
+
+
+def plinear_bwd(dY, X, W, Yhat, r: Routing, k: int, gates=None, grouped_in=False, grouped_out=False,
+                need_dX=True, need_dW=True):
+    """Alg. 2.  Returns (dX, dW, dgates)."""
+    _chk(dY, X.dtype); _chk(X); _chk(W, X.dtype)
+    d_in, d_out = W.shape[1], W.shape[2]
+    dX = torch.empty_like(X) if need_dX else None
+    dW = torch.empty_like(W) if need_dW else None
+    dg, gk = None, 0
+    if gates is not None:
+        _chk(gates, torch.float32)
+        gk = gates.shape[1]
+        dg = torch.empty_like(gates)
+    nb = lib.smoe_plinear_bwd_workspace_bytes(_dt(X), X.shape[0], d_in, d_out, r.Tk, k, int(gates is not None),
+                                              int(grouped_in), int(grouped_out))
+    ws = _ws(nb, X.device)
+    rc = r.c()
+    _check(lib.smoe_plinear_bwd(ctx(), _stream(), _dt(X), _p(dY), _p(X), X.shape[0], d_in, _p(W), d_out, _p(Yhat),
+                                ctypes.byref(rc), k, _p(gates), gk, int(grouped_in), int(grouped_out), _p(dX), _p(dW),
+                                _p(dg), _p(ws), ws.numel()), "smoe_plinear_bwd")
+    return dX, dW, dg
+
+
+def hidden_width(act: int, d_expert: int) -> int:
+    return 2 * d_expert if act == ACT_SWIGLU else d_expert
+
+
+class MLPBuffers:
+    """Preallocated outputs, saved activations and scratch of one SMoE MLP shape, so that
+    repeated calls (training steps, benchmarks) do not allocate."""
+
+    def __init__(self, T, k, E, d_model, d_expert, act, dtype, device, training=True):
+        Tk, d_h = T * k, hidden_width(act, d_expert)
+        dt = F32 if dtype == torch.float32 else BF16
+        mk = lambda *s: torch.empty(*s, dtype=dtype, device=device)
+        self.T, self.k, self.E, self.d_model, self.d_expert, self.act, self.dtype = T, k, E, d_model, d_expert, act, dtype
+        self.Y = mk(T, d_model)
+        self.training = training
+        if training:
+            self.Hpre, self.H, self.Yhat = mk(Tk, d_h), mk(Tk, d_expert), mk(Tk, d_model)
+            self.dX, self.dW1, self.dW2 = mk(T, d_model), mk(E, d_model, d_h), mk(E, d_expert, d_model)
+            self.dgates = torch.empty(T, k, dtype=torch.float32, device=device)
+            self.ws_bwd = _ws(lib.smoe_mlp_bwd_workspace_bytes(dt, act, T, k, d_model, d_expert), device)
+        else:
+            self.Hpre = self.H = self.Yhat = None
+        self.ws_fwd = _ws(lib.smoe_mlp_fwd_workspace_bytes(dt, act, T, k, d_model, d_expert, int(training)), device)
+
+
+def mlp_fwd(X, W1, W2, r: Routing, k: int, gates, act: int, buf: MLPBuffers | None = None, training=True):
+    """Alg. 3.  Returns (Y, buf); buf carries the tensors the backward pass needs."""
+    _chk(X); _chk(W1, X.dtype); _chk(W2, X.dtype); _chk(gates, torch.float32)
+    T, d_model = X.shape
+    E, d_expert = W2.shape[0], W2.shape[1]
+    if buf is None:
+        buf = MLPBuffers(T, k, E, d_model, d_expert, act, X.dtype, X.device, training)
+    rc = r.c()
+    _check(lib.smoe_mlp_fwd(ctx(), _stream(), _dt(X), act, _p(X), T, d_model, d_expert, _p(W1), _p(W2),
+                            ctypes.byref(rc), k, _p(gates), _p(buf.Y), _p(buf.Hpre), _p(buf.H), _p(buf.Yhat),
+                            _p(buf.ws_fwd), buf.ws_fwd.numel()), "smoe_mlp_fwd")
+    return buf.Y, buf
+
+
+def mlp_bwd(dY, X, W1, W2, r: Routing, k: int, gates, act: int, buf: MLPBuffers):
+    """Backward of mlp_fwd.  Returns (dX, dW1, dW2, dgates), views of buf."""
+    _chk(dY, X.dtype)
+    T, d_model = X.shape
+    d_expert = W2.shape[1]
+    rc = r.c()
+    _check(lib.smoe_mlp_bwd(ctx(), _stream(), _dt(X), act, _p(dY), _p(X), T, d_model, d_expert, _p(W1), _p(W2),
+                            ctypes.byref(rc), k, _p(gates), _p(buf.Hpre), _p(buf.H), _p(buf.Yhat), _p(buf.dX),
+                            _p(buf.dW1), _p(buf.dW2), _p(buf.dgates), _p(buf.ws_bwd), buf.ws_bwd.numel()),
+           "smoe_mlp_bwd")
+    return buf.dX, buf.dW1, buf.dW2, buf.dgates

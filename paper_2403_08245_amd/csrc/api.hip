@@ -1,0 +1,360 @@
+// C ABI of libsmoe: argument checks, workspace layout and the order of kernel launches for
+// ParallelLinear (Alg. 1, Alg. 2) and the SMoE MLP (Alg. 3).  No entry point allocates,
+// synchronises or touches the host copy of any tensor.
+#include "common.h"
+#include <new>
+
+namespace {
+inline bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+bool routing_ok(const smoe_routing *r) {
+  if (!r || r->Tk < 0 || r->E < 1 || !r->expert_offsets) return false;
+  return r->Tk == 0 || (r->sorted_expert_idxs && r->sorted_scattered_idxs);  // empty index arrays may be null
+}
+// Row widths must allow 16-byte accesses in the row kernels.
+bool width_ok(smoe_dtype dt, int d) { return d > 0 && d % (int)(16 / dtype_size(dt)) == 0; }
+bool dtype_ok(int dt) { return dt == SMOE_F32 || dt == SMOE_BF16; }
+
+int run_s2s(smoe_ctx *ctx, hipStream_t s, smoe_dtype dt, const S2SArgs &a) {
+  if (dt == SMOE_BF16 && ctx->kernel_mode == 0 && s2s_mfma_supported(a)) return launch_s2s_mfma(s, a, ctx->num_cu);
+  return launch_s2s_plain(s, dt, a);
+}
+int run_dw(smoe_ctx *ctx, hipStream_t s, smoe_dtype dt, const DWArgs &a) {
+  if (dt == SMOE_BF16 && ctx->kernel_mode == 0 && dw_mfma_supported(a)) return launch_dw_mfma(s, a, ctx->num_cu);
+  return launch_dw_plain(s, dt, a);
+}
+
+S2SArgs make_s2s(const void *A, const void *W, void *C, const smoe_routing *r, int d_in, int d_out, bool trans_w,
+                 bool a_grouped, int a_fan, bool c_grouped) {
+  S2SArgs a;
+  a.A = A; a.W = W; a.C = C;
+  a.a_map = RowMap{a_grouped ? nullptr : r->sorted_scattered_idxs, a_fan};
+  a.c_map = RowMap{c_grouped ? nullptr : r->sorted_scattered_idxs, 1};
+  a.offsets = r->expert_offsets;
+  a.E = r->E; a.Tk = r->Tk;
+  a.K = trans_w ? d_out : d_in;
+  a.N = trans_w ? d_in : d_out;
+  a.ldw = d_out;
+  a.w_stride = (size_t)d_in * d_out;
+  a.trans_w = trans_w ? 1 : 0;
+  return a;
+}
+}  // namespace
+
+extern "C" {
+
+int smoe_abi_version(void) { return 1; }
+
+const char *smoe_strerror(int status) {
+  switch (status) {
+    case SMOE_OK: return "ok";
+    case SMOE_ERR_INVALID_ARG: return "invalid argument";
+    case SMOE_ERR_UNSUPPORTED: return "unsupported shape or option (row widths must be multiples of 16 bytes)";
+    case SMOE_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case SMOE_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int smoe_create(smoe_ctx **out, int device) {
+  if (!out) return SMOE_ERR_INVALID_ARG;
+  *out = nullptr;
+  int count = 0;
+  if (hipGetDeviceCount(&count) != hipSuccess) return SMOE_ERR_HIP;
+  if (device < 0 || device >= count) return SMOE_ERR_INVALID_ARG;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, device) != hipSuccess) return SMOE_ERR_HIP;
+  smoe_ctx *c = new (std::nothrow) smoe_ctx;
+  if (!c) return SMOE_ERR_HIP;
+  c->device = device;
+  c->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  c->kernel_mode = 0;
+  *out = c;
+  return SMOE_OK;
+}
+
+void smoe_destroy(smoe_ctx *ctx) { delete ctx; }
+
+int smoe_set_kernel_mode(smoe_ctx *ctx, int mode) {
+  if (!ctx || mode < 0 || mode > 1) return SMOE_ERR_INVALID_ARG;
+  ctx->kernel_mode = mode;
+  return SMOE_OK;
+}
+
+int smoe_topk_gate(smoe_ctx *ctx, void *stream, const float *logits, int T, int E, int k, int32_t *expert_idxs,
+                   float *gates) {
+  if (!ctx || T < 0 || E < 1 || k < 1 || k > E) return SMOE_ERR_INVALID_ARG;
+  if (T == 0) return SMOE_OK;
+  if (!logits || !expert_idxs || !gates) return SMOE_ERR_INVALID_ARG;
+  if ((long long)T * k > 0x7fffffffLL) return SMOE_ERR_UNSUPPORTED;
+  return launch_topk_gate((hipStream_t)stream, logits, T, E, k, expert_idxs, gates);
+}
+
+size_t smoe_route_workspace_bytes(int T, int k, int E) {
+  if (T < 0 || k < 1 || E < 1) return 0;
+  return route_workspace_bytes(T * k, E);
+}
+
+int smoe_route(smoe_ctx *ctx, void *stream, const int32_t *expert_idxs, int T, int k, int E,
+               int32_t *sorted_expert_idxs, int32_t *sorted_scattered_idxs, int32_t *expert_offsets, void *ws,
+               size_t ws_bytes) {
+  if (!ctx || T < 0 || k < 1 || E < 1 || !expert_offsets) return SMOE_ERR_INVALID_ARG;
+  if ((long long)T * k > 0x7fffffffLL) return SMOE_ERR_UNSUPPORTED;
+  if (T > 0 && (!expert_idxs || !sorted_expert_idxs || !sorted_scattered_idxs)) return SMOE_ERR_INVALID_ARG;
+  if (!ws || ((uintptr_t)ws & 255) || ws_bytes < route_workspace_bytes(T * k, E)) return SMOE_ERR_WORKSPACE;
+  return launch_route((hipStream_t)stream, expert_idxs, T * k, E, sorted_expert_idxs, sorted_scattered_idxs,
+                      expert_offsets, ws);
+}
+
+int smoe_group(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *in, int d, const smoe_routing *r, int fan,
+               const float *gates, void *out) {
+  if (!ctx || !dtype_ok(dtype) || !routing_ok(r) || fan < 1 || d < 1) return SMOE_ERR_INVALID_ARG;
+  if (r->Tk == 0) return SMOE_OK;
+  if (!in || !out || r->Tk % fan) return SMOE_ERR_INVALID_ARG;
+  if (!width_ok(dtype, d) || !aligned16(in) || !aligned16(out)) return SMOE_ERR_UNSUPPORTED;
+  return launch_group((hipStream_t)stream, dtype, in, r->sorted_scattered_idxs, fan, gates, out, r->Tk, d);
+}
+
+// ------------------------------------------------------------------------------ Alg. 1
+int smoe_plinear_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *X, int x_rows, int d_in,
+                     const void *W, int d_out, const smoe_routing *r, int k, const float *gates, int gates_k,
+                     int grouped_in, int grouped_out, void *Yhat, void *Y) {
+  if (!ctx || !dtype_ok(dtype) || !routing_ok(r) || d_in < 1 || d_out < 1 || k < 1 || x_rows < 0)
+    return SMOE_ERR_INVALID_ARG;
+  const int Tk = r->Tk;
+  if (grouped_in ? (k != 1 || x_rows != Tk) : ((long long)x_rows * k != Tk)) return SMOE_ERR_INVALID_ARG;
+  if (gates) {
+    if (grouped_out || gates_k < 1 || Tk % gates_k || !Y) return SMOE_ERR_INVALID_ARG;
+  } else if (Y) {
+    return SMOE_ERR_INVALID_ARG;
+  }
+  if (Tk == 0) return SMOE_OK;
+  if (!X || !W || !Yhat) return SMOE_ERR_INVALID_ARG;
+  if (!width_ok(dtype, d_in) || !width_ok(dtype, d_out) || !aligned16(X) || !aligned16(W) || !aligned16(Yhat) ||
+      (Y && !aligned16(Y)))
+    return SMOE_ERR_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  S2SArgs a = make_s2s(X, W, Yhat, r, d_in, d_out, false, grouped_in != 0, k, grouped_out != 0);
+  int rc = run_s2s(ctx, s, dtype, a);
+  if (rc != SMOE_OK) return rc;
+  if (gates) rc = launch_combine(s, dtype, Yhat, gates, Y, Tk / gates_k, gates_k, d_out);
+  return rc;
+}
+
+// ------------------------------------------------------------------------------ Alg. 2
+// Workspace: [dYbar: Tk x d_out, only if dY arrives scattered with gates]
+//            [dXbar: Tk x d_in, only if X was scattered with fan-out > 1]
+static void plinear_bwd_layout(smoe_dtype dt, int d_in, int d_out, int Tk, int k, int has_gates, int grouped_in,
+                               size_t &off_dybar, size_t &off_dxbar, size_t &total) {
+  size_t es = dtype_size(dt), off = 0;
+  off_dybar = off_dxbar = (size_t)-1;
+  if (has_gates) { off_dybar = off; off += align256((size_t)Tk * d_out * es); }
+  if (!grouped_in && k > 1) { off_dxbar = off; off += align256((size_t)Tk * d_in * es); }
+  total = off;
+}
+
+size_t smoe_plinear_bwd_workspace_bytes(smoe_dtype dtype, int x_rows, int d_in, int d_out, int Tk, int k,
+                                        int has_gates, int grouped_in, int grouped_out) {
+  (void)x_rows; (void)grouped_out;
+  if (!dtype_ok(dtype) || d_in < 1 || d_out < 1 || Tk < 0 || k < 1) return 0;
+  size_t a, b, total;
+  plinear_bwd_layout(dtype, d_in, d_out, Tk, k, has_gates, grouped_in, a, b, total);
+  return total;
+}
+
+int smoe_plinear_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *dY, const void *X, int x_rows,
+                     int d_in, const void *W, int d_out, const void *Yhat, const smoe_routing *r, int k,
+                     const float *gates, int gates_k, int grouped_in, int grouped_out, void *dX, void *dW,
+                     float *dgates, void *ws, size_t ws_bytes) {
+  if (!ctx || !dtype_ok(dtype) || !routing_ok(r) || d_in < 1 || d_out < 1 || k < 1 || x_rows < 0)
+    return SMOE_ERR_INVALID_ARG;
+  const int Tk = r->Tk;
+  if (grouped_in ? (k != 1 || x_rows != Tk) : ((long long)x_rows * k != Tk)) return SMOE_ERR_INVALID_ARG;
+  if (gates && (grouped_out || gates_k < 1 || Tk % gates_k)) return SMOE_ERR_INVALID_ARG;
+  if (!gates && dgates) return SMOE_ERR_INVALID_ARG;
+  if (dgates && !Yhat) return SMOE_ERR_INVALID_ARG;
+  if (!width_ok(dtype, d_in) || !width_ok(dtype, d_out)) return SMOE_ERR_UNSUPPORTED;
+  if (!W && dX) return SMOE_ERR_INVALID_ARG;
+  size_t off_dybar, off_dxbar, need;
+  plinear_bwd_layout(dtype, d_in, d_out, Tk, k, gates != nullptr, grouped_in, off_dybar, off_dxbar, need);
+  if (need && (!ws || ((uintptr_t)ws & 255) || ws_bytes < need)) return SMOE_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  int rc = SMOE_OK;
+  if (Tk == 0) {  // no routed rows: dW is all zeros, nothing else to write
+    if (dW) {
+      DWArgs z{nullptr, nullptr, dW, RowMap{nullptr, 1}, RowMap{nullptr, 1}, r->expert_offsets, r->E, 0, d_in, d_out};
+      rc = launch_dw_plain(s, dtype, z);
+    }
+    return rc;
+  }
+  if (!dY || !X) return SMOE_ERR_INVALID_ARG;
+  if (!aligned16(dY) || !aligned16(X) || (W && !aligned16(W)) || (dX && !aligned16(dX)) || (dW && !aligned16(dW)))
+    return SMOE_ERR_UNSUPPORTED;
+
+  // dp = bmm(dY, Yhat), then the weighted group of dY (Alg. 2, first branch).
+  const void *dYsrc = dY;          // rows feeding the two GEMMs
+  bool dy_grouped = grouped_out != 0;
+  int dy_fan = 1;
+  if (gates) {
+    if (dgates) {
+      rc = launch_rowdot(s, dtype, dY, Yhat, dgates, Tk, gates_k, d_out);
+      if (rc != SMOE_OK) return rc;
+    }
+    void *dYbar = (char *)ws + off_dybar;
+    rc = launch_group(s, dtype, dY, r->sorted_scattered_idxs, gates_k, gates, dYbar, Tk, d_out);
+    if (rc != SMOE_OK) return rc;
+    dYsrc = dYbar;
+    dy_grouped = true;
+  }
+  // dW = groupXTY(Xbar, dYbar); X and an unweighted scattered dY are gathered by the kernel
+  // itself instead of being copied into grouped order first.
+  if (dW) {
+    DWArgs a;
+    a.A = X; a.B = dYsrc; a.dW = dW;
+    a.a_map = RowMap{grouped_in ? nullptr : r->sorted_scattered_idxs, k};
+    a.b_map = RowMap{dy_grouped ? nullptr : r->sorted_scattered_idxs, dy_fan};
+    a.offsets = r->expert_offsets;
+    a.E = r->E; a.Tk = Tk; a.M = d_in; a.N = d_out;
+    rc = run_dw(ctx, s, dtype, a);
+    if (rc != SMOE_OK) return rc;
+  }
+  // dXbar = scatter2scatter(dYbar, W^T, o, 1): grouped or scattered like the forward input.
+  if (dX) {
+    bool need_sum = !grouped_in && k > 1;
+    void *dst = need_sum ? (void *)((char *)ws + off_dxbar) : dX;
+    S2SArgs a = make_s2s(dYsrc, W, dst, r, d_in, d_out, true, dy_grouped, dy_fan, grouped_in != 0);
+    rc = run_s2s(ctx, s, dtype, a);
+    if (rc != SMOE_OK) return rc;
+    if (need_sum) rc = launch_combine(s, dtype, dst, nullptr, dX, x_rows, k, d_in);
+  }
+  return rc;
+}
+
+// ------------------------------------------------------------------------------ Alg. 3
+static inline int hidden_width(smoe_act act, int d_expert) { return act == SMOE_ACT_SWIGLU ? 2 * d_expert : d_expert; }
+
+size_t smoe_mlp_fwd_workspace_bytes(smoe_dtype dtype, smoe_act act, int T, int k, int d_model, int d_expert,
+                                    int training) {
+  if (!dtype_ok(dtype) || T < 0 || k < 1 || d_model < 1 || d_expert < 1) return 0;
+  if (training) return 0;
+  size_t es = dtype_size(dtype), Tk = (size_t)T * k;
+  return align256(Tk * hidden_width(act, d_expert) * es) + align256(Tk * d_expert * es) + align256(Tk * d_model * es);
+}
+
+int smoe_mlp_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, const void *X, int T, int d_model,
+                 int d_expert, const void *W1, const void *W2, const smoe_routing *r, int k, const float *gates,
+                 void *Y, void *saved_Hpre, void *saved_H, void *saved_Yhat, void *ws, size_t ws_bytes) {
+  if (!ctx || !dtype_ok(dtype) || !routing_ok(r) || T < 0 || k < 1 || d_model < 1 || d_expert < 1)
+    return SMOE_ERR_INVALID_ARG;
+  if (act != SMOE_ACT_NONE && act != SMOE_ACT_GELU && act != SMOE_ACT_SWIGLU) return SMOE_ERR_INVALID_ARG;
+  if ((long long)T * k != r->Tk) return SMOE_ERR_INVALID_ARG;
+  int nsaved = (saved_Hpre != nullptr) + (saved_H != nullptr) + (saved_Yhat != nullptr);
+  if (nsaved != 0 && nsaved != 3) return SMOE_ERR_INVALID_ARG;
+  if (T == 0) return SMOE_OK;
+  if (!X || !W1 || !W2 || !gates || !Y) return SMOE_ERR_INVALID_ARG;
+  const int d_h = hidden_width(act, d_expert), Tk = r->Tk;
+  if (!width_ok(dtype, d_model) || !width_ok(dtype, d_expert)) return SMOE_ERR_UNSUPPORTED;
+  size_t es = dtype_size(dtype);
+  if (nsaved == 0) {
+    size_t need = smoe_mlp_fwd_workspace_bytes(dtype, act, T, k, d_model, d_expert, 0);
+    if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need) return SMOE_ERR_WORKSPACE;
+    saved_Hpre = ws;
+    saved_H = (char *)saved_Hpre + align256((size_t)Tk * d_h * es);
+    saved_Yhat = (char *)saved_H + align256((size_t)Tk * d_expert * es);
+  }
+  if (!aligned16(X) || !aligned16(W1) || !aligned16(W2) || !aligned16(Y) || !aligned16(saved_Hpre) ||
+      !aligned16(saved_H) || !aligned16(saved_Yhat))
+    return SMOE_ERR_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  // Hpre = ParallelLinear(X, W1, scattered -> grouped)
+  S2SArgs a1 = make_s2s(X, W1, saved_Hpre, r, d_model, d_h, false, false, k, true);
+  int rc = run_s2s(ctx, s, dtype, a1);
+  if (rc != SMOE_OK) return rc;
+  // H = sigma(Hpre)
+  rc = launch_act_fwd(s, dtype, act, saved_Hpre, saved_H, Tk, d_expert);
+  if (rc != SMOE_OK) return rc;
+  // Y = ParallelLinear(H, W2, p, grouped -> scattered)
+  S2SArgs a2 = make_s2s(saved_H, W2, saved_Yhat, r, d_expert, d_model, false, true, 1, false);
+  rc = run_s2s(ctx, s, dtype, a2);
+  if (rc != SMOE_OK) return rc;
+  return launch_combine(s, dtype, saved_Yhat, gates, Y, T, k, d_model);
+}
+
+// Workspace of the backward pass: dYbar [Tk,d_model] (later reused for dXbar), dH [Tk,d_expert],
+// dHpre [Tk,d_h].
+size_t smoe_mlp_bwd_workspace_bytes(smoe_dtype dtype, smoe_act act, int T, int k, int d_model, int d_expert) {
+  if (!dtype_ok(dtype) || T < 0 || k < 1 || d_model < 1 || d_expert < 1) return 0;
+  size_t es = dtype_size(dtype), Tk = (size_t)T * k;
+  return align256(Tk * d_model * es) + align256(Tk * d_expert * es) + align256(Tk * hidden_width(act, d_expert) * es);
+}
+
+int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, const void *dY, const void *X, int T,
+                 int d_model, int d_expert, const void *W1, const void *W2, const smoe_routing *r, int k,
+                 const float *gates, const void *saved_Hpre, const void *saved_H, const void *saved_Yhat, void *dX,
+                 void *dW1, void *dW2, float *dgates, void *ws, size_t ws_bytes) {
+  if (!ctx || !dtype_ok(dtype) || !routing_ok(r) || T < 0 || k < 1 || d_model < 1 || d_expert < 1)
+    return SMOE_ERR_INVALID_ARG;
+  if (act != SMOE_ACT_NONE && act != SMOE_ACT_GELU && act != SMOE_ACT_SWIGLU) return SMOE_ERR_INVALID_ARG;
+  if ((long long)T * k != r->Tk) return SMOE_ERR_INVALID_ARG;
+  if (!dW1 || !dW2) return SMOE_ERR_INVALID_ARG;
+  if (!width_ok(dtype, d_model) || !width_ok(dtype, d_expert)) return SMOE_ERR_UNSUPPORTED;
+  const int d_h = hidden_width(act, d_expert), Tk = r->Tk;
+  size_t es = dtype_size(dtype);
+  size_t need = smoe_mlp_bwd_workspace_bytes(dtype, act, T, k, d_model, d_expert);
+  if (need && (!ws || ((uintptr_t)ws & 255) || ws_bytes < need)) return SMOE_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  int rc;
+  if (T == 0) {
+    DWArgs z1{nullptr, nullptr, dW1, RowMap{nullptr, 1}, RowMap{nullptr, 1}, r->expert_offsets, r->E, 0, d_model, d_h};
+    rc = launch_dw_plain(s, dtype, z1);
+    if (rc != SMOE_OK) return rc;
+    DWArgs z2{nullptr, nullptr, dW2, RowMap{nullptr, 1}, RowMap{nullptr, 1}, r->expert_offsets, r->E, 0, d_expert, d_model};
+    return launch_dw_plain(s, dtype, z2);
+  }
+  if (!dY || !X || !W1 || !W2 || !gates || !saved_Hpre || !saved_H || !saved_Yhat || !dX || !dgates)
+    return SMOE_ERR_INVALID_ARG;
+  if (!aligned16(dY) || !aligned16(X) || !aligned16(W1) || !aligned16(W2) || !aligned16(saved_Hpre) ||
+      !aligned16(saved_H) || !aligned16(saved_Yhat) || !aligned16(dX) || !aligned16(dW1) || !aligned16(dW2))
+    return SMOE_ERR_UNSUPPORTED;
+  char *p = (char *)ws;
+  void *dYbar = p;                 p += align256((size_t)Tk * d_model * es);
+  void *dH = p;                    p += align256((size_t)Tk * d_expert * es);
+  void *dHpre = p;
+  void *dXbar = dYbar;  // dYbar is dead once dH and dW2 are done
+
+  // ---- second ParallelLinear (grouped in, scattered weighted out)
+  rc = launch_rowdot(s, dtype, dY, saved_Yhat, dgates, Tk, k, d_model);                 // dp = bmm(dY, Yhat)
+  if (rc != SMOE_OK) return rc;
+  rc = launch_group(s, dtype, dY, r->sorted_scattered_idxs, k, gates, dYbar, Tk, d_model);  // weight and group
+  if (rc != SMOE_OK) return rc;
+  DWArgs w2;
+  w2.A = saved_H; w2.B = dYbar; w2.dW = dW2;
+  w2.a_map = RowMap{nullptr, 1}; w2.b_map = RowMap{nullptr, 1};
+  w2.offsets = r->expert_offsets; w2.E = r->E; w2.Tk = Tk; w2.M = d_expert; w2.N = d_model;
+  rc = run_dw(ctx, s, dtype, w2);                                                      // groupXTY
+  if (rc != SMOE_OK) return rc;
+  S2SArgs x2 = make_s2s(dYbar, W2, dH, r, d_expert, d_model, true, true, 1, true);      // dH = dYbar W2^T
+  rc = run_s2s(ctx, s, dtype, x2);
+  if (rc != SMOE_OK) return rc;
+  // ---- activation
+  rc = launch_act_bwd(s, dtype, act, saved_Hpre, dH, dHpre, Tk, d_expert);
+  if (rc != SMOE_OK) return rc;
+  // ---- first ParallelLinear (scattered in with fan-out k, grouped out): X rows are
+  //      gathered inside groupXTY, so no grouped copy of X is made.
+  DWArgs w1;
+  w1.A = X; w1.B = dHpre; w1.dW = dW1;
+  w1.a_map = RowMap{r->sorted_scattered_idxs, k}; w1.b_map = RowMap{nullptr, 1};
+  w1.offsets = r->expert_offsets; w1.E = r->E; w1.Tk = Tk; w1.M = d_model; w1.N = d_h;
+  rc = run_dw(ctx, s, dtype, w1);
+  if (rc != SMOE_OK) return rc;
+  if (k == 1) {  // slot id == token id: scatter straight into dX
+    S2SArgs x1 = make_s2s(dHpre, W1, dX, r, d_model, d_h, true, true, 1, false);
+    return run_s2s(ctx, s, dtype, x1);
+  }
+  S2SArgs x1 = make_s2s(dHpre, W1, dXbar, r, d_model, d_h, true, true, 1, false);       // grouped -> scattered
+  rc = run_s2s(ctx, s, dtype, x1);
+  if (rc != SMOE_OK) return rc;
+  return launch_combine(s, dtype, dXbar, nullptr, dX, T, k, d_model);                   // sum the k slots
+}
+
+}  // extern "C"

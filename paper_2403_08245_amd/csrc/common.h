@@ -1,0 +1,86 @@
+// Shared declarations of the libsmoe kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "smoe.h"
+
+typedef __bf16 bf16_t;
+
+struct smoe_ctx {
+  int device;
+  int num_cu;
+  int kernel_mode;  // 0 auto, 1 plain tiled kernels only
+};
+
+#define SMOE_LAUNCH_CHECK()                                   \
+  do {                                                        \
+    if (hipGetLastError() != hipSuccess) return SMOE_ERR_HIP; \
+  } while (0)
+
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+static inline size_t dtype_size(smoe_dtype d) { return d == SMOE_BF16 ? 2 : 4; }
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+template <typename T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }  // RNE
+
+// How a GEMM operand's rows are addressed through the routing arrays.
+//   sorted position i -> row i (grouped) or o[i] / fan (scattered source with fan-out)
+//   or o[i] (scattered destination).
+struct RowMap {
+  const int32_t *o;  // sorted_scattered_idxs, or nullptr when rows are already grouped
+  int fan;           // divisor applied to o[i]; 1 for slot-indexed tensors
+};
+__device__ __forceinline__ int map_row(const RowMap &m, int i) {
+  return m.o ? (m.fan > 1 ? m.o[i] / m.fan : m.o[i]) : i;
+}
+
+// ---- routing.hip
+int launch_topk_gate(hipStream_t s, const float *logits, int T, int E, int k, int32_t *idx, float *gates);
+size_t route_workspace_bytes(int Tk, int E);
+int launch_route(hipStream_t s, const int32_t *expert_idxs, int Tk, int E, int32_t *sorted_e,
+                 int32_t *sorted_s, int32_t *offsets, void *ws);
+
+// ---- elementwise.hip
+int launch_act_fwd(hipStream_t s, smoe_dtype dt, smoe_act act, const void *Hpre, void *H, int rows, int d_expert);
+int launch_act_bwd(hipStream_t s, smoe_dtype dt, smoe_act act, const void *Hpre, const void *dH, void *dHpre,
+                   int rows, int d_expert);
+// Y[t] = sum_j g[t*k+j] * Yhat[t*k+j]; g == nullptr means all ones.
+int launch_combine(hipStream_t s, smoe_dtype dt, const void *Yhat, const float *g, void *Y, int T, int k, int d);
+int launch_group(hipStream_t s, smoe_dtype dt, const void *in, const int32_t *o, int fan, const float *g,
+                 void *out, int Tk, int d);
+// dg[s] = <dY[s / kp], Yhat[s]>
+int launch_rowdot(hipStream_t s, smoe_dtype dt, const void *dY, const void *Yhat, float *dg, int Tk, int kp, int d);
+
+// ---- GEMM launchers (gemm_plain.hip, gemm_mfma.hip)
+struct S2SArgs {      // C[out(i), :] = A[in(i), :] * op(W[e(i)])   for sorted rows i
+  const void *A;      // [*, K] rows addressed through a_map
+  const void *W;      // [E, d_in, d_out]
+  void *C;            // [*, N] rows addressed through c_map
+  RowMap a_map, c_map;
+  const int32_t *offsets;  // [E+1]
+  int E, Tk;
+  int K, N;           // contraction length and output width
+  int ldw;            // row stride of W[e] (= d_out)
+  size_t w_stride;    // elements between experts (= d_in * d_out)
+  int trans_w;        // 0: op(W) = W (K = d_in, N = d_out); 1: op(W) = W^T (K = d_out, N = d_in)
+};
+struct DWArgs {       // dW[e] = sum_{i in segment e} A[a(i), :]^T B[b(i), :]
+  const void *A;      // [*, M]
+  const void *B;      // [*, N]
+  void *dW;           // [E, M, N]
+  RowMap a_map, b_map;
+  const int32_t *offsets;
+  int E, Tk, M, N;
+};
+int launch_s2s_plain(hipStream_t s, smoe_dtype dt, const S2SArgs &a);
+int launch_dw_plain(hipStream_t s, smoe_dtype dt, const DWArgs &a);
+bool s2s_mfma_supported(const S2SArgs &a);
+bool dw_mfma_supported(const DWArgs &a);
+int launch_s2s_mfma(hipStream_t s, const S2SArgs &a, int num_cu);
+int launch_dw_mfma(hipStream_t s, const DWArgs &a, int num_cu);

@@ -1,0 +1,156 @@
+// Routing kernels: top-k gate (Sec. 3.1 step 1) and the stable bucket sort of the routed
+// slots by expert (Sec. 3.1 step 2), integer-exact.
+#include "common.h"
+
+// ---------------------------------------------------------------------------------------
+// top-k gate: one thread per token.  Slot j takes the largest logit that comes after slot
+// j-1's pick in the order (value descending, expert id ascending), so ties go to the lower
+// id and no per-thread array is needed.  Gates are the softmax over the k picks.
+// ---------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) topk_gate_kernel(const float *__restrict__ logits, int T, int E, int k,
+                                                        int32_t *__restrict__ idx, float *__restrict__ gates) {
+  int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T) return;
+  const float *row = logits + (size_t)t * E;
+  float prev_v = 0.f, first_v = 0.f, sum = 0.f;
+  int prev_i = -1;
+  for (int j = 0; j < k; ++j) {
+    float best_v = 0.f;
+    int best_i = -1;
+    for (int e = 0; e < E; ++e) {
+      float v = row[e];
+      bool after_prev = (prev_i < 0) || (v < prev_v) || (v == prev_v && e > prev_i);
+      bool better = (best_i < 0) || (v > best_v);  // first hit wins ties -> lower id
+      if (after_prev && better) { best_v = v; best_i = e; }
+    }
+    if (j == 0) first_v = best_v;
+    float w = expf(best_v - first_v);
+    idx[(size_t)t * k + j] = best_i;
+    gates[(size_t)t * k + j] = w;
+    sum += w;
+    prev_v = best_v;
+    prev_i = best_i;
+  }
+  float inv = 1.0f / sum;
+  for (int j = 0; j < k; ++j) gates[(size_t)t * k + j] *= inv;
+}
+
+int launch_topk_gate(hipStream_t s, const float *logits, int T, int E, int k, int32_t *idx, float *gates) {
+  if (T == 0) return SMOE_OK;
+  hipLaunchKernelGGL(topk_gate_kernel, dim3(ceil_div(T, 256)), dim3(256), 0, s, logits, T, E, k, idx, gates);
+  SMOE_LAUNCH_CHECK();
+  return SMOE_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// Stable bucket sort by expert in three launches:
+//   1. each 64-lane block counts the experts of its contiguous chunk of slots,
+//   2. one block turns the [chunk][expert] counts into start positions (expert-major
+//      exclusive scan) and writes expert_offsets,
+//   3. each block walks its chunk again 64 slots at a time; a lane's rank among the lanes
+//      of the same expert comes from wavefront ballots over the bits of the expert id.
+// Slots keep their order inside an expert because chunks, steps and lanes are all visited
+// in ascending slot order.
+// ---------------------------------------------------------------------------------------
+static constexpr int ROUTE_CHUNK = 1024;  // slots per block
+
+__device__ __forceinline__ int clamp_expert(int e, int E) { return e < 0 ? 0 : (e >= E ? E - 1 : e); }
+
+__global__ void __launch_bounds__(64) route_count_kernel(const int32_t *__restrict__ expert_idxs, int Tk, int E,
+                                                         int32_t *__restrict__ counts /*[nchunk][E]*/) {
+  extern __shared__ int32_t hist[];
+  for (int e = threadIdx.x; e < E; e += 64) hist[e] = 0;
+  __syncthreads();
+  int base = blockIdx.x * ROUTE_CHUNK;
+  int end = min(base + ROUTE_CHUNK, Tk);
+  for (int s = base + threadIdx.x; s < end; s += 64) atomicAdd(&hist[clamp_expert(expert_idxs[s], E)], 1);
+  __syncthreads();
+  for (int e = threadIdx.x; e < E; e += 64) counts[(size_t)blockIdx.x * E + e] = hist[e];
+}
+
+// counts[c][e] -> start position of (c, e); offsets[e] = rows before expert e.
+__global__ void __launch_bounds__(256) route_scan_kernel(int32_t *__restrict__ counts, int nchunk, int E,
+                                                         int32_t *__restrict__ offsets, int Tk) {
+  extern __shared__ int32_t totals[];  // [E] rows per expert, then exclusive prefix
+  for (int e = threadIdx.x; e < E; e += blockDim.x) {
+    int sum = 0;
+    for (int c = 0; c < nchunk; ++c) sum += counts[(size_t)c * E + e];
+    totals[e] = sum;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int e = 0; e < E; ++e) {
+      int n = totals[e];
+      totals[e] = run;
+      offsets[e] = run;
+      run += n;
+    }
+    offsets[E] = run;
+  }
+  __syncthreads();
+  for (int e = threadIdx.x; e < E; e += blockDim.x) {
+    int run = totals[e];
+    for (int c = 0; c < nchunk; ++c) {
+      int n = counts[(size_t)c * E + e];
+      counts[(size_t)c * E + e] = run;
+      run += n;
+    }
+  }
+}
+
+__global__ void __launch_bounds__(64) route_place_kernel(const int32_t *__restrict__ expert_idxs, int Tk, int E,
+                                                         const int32_t *__restrict__ starts /*[nchunk][E]*/,
+                                                         int32_t *__restrict__ sorted_e,
+                                                         int32_t *__restrict__ sorted_s) {
+  extern __shared__ int32_t next[];  // next free position per expert for this chunk
+  for (int e = threadIdx.x; e < E; e += 64) next[e] = starts[(size_t)blockIdx.x * E + e];
+  __syncthreads();
+  int nbits = 32 - __clz(max(E - 1, 1));
+  int base = blockIdx.x * ROUTE_CHUNK;
+  int end = min(base + ROUTE_CHUNK, Tk);
+  int lane = threadIdx.x;
+  unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  for (int s0 = base; s0 < end; s0 += 64) {
+    int s = s0 + lane;
+    bool live = s < end;
+    int e = live ? clamp_expert(expert_idxs[s], E) : 0;
+    unsigned long long peers = __ballot(live);
+    for (int b = 0; b < nbits; ++b) {
+      unsigned long long set = __ballot(live && ((e >> b) & 1));
+      peers &= ((e >> b) & 1) ? set : ~set;
+    }
+    int rank = __popcll(peers & lt_mask);
+    int pos = 0;
+    if (live) pos = next[e] + rank;
+    __syncthreads();
+    if (live && rank == 0) next[e] += __popcll(peers);  // lowest lane of each expert updates
+    __syncthreads();
+    if (live) {
+      sorted_e[pos] = e;
+      sorted_s[pos] = s;
+    }
+  }
+}
+
+size_t route_workspace_bytes(int Tk, int E) {
+  size_t nchunk = (size_t)ceil_div(Tk > 0 ? Tk : 1, ROUTE_CHUNK);
+  return align256(nchunk * (size_t)E * sizeof(int32_t));
+}
+
+int launch_route(hipStream_t s, const int32_t *expert_idxs, int Tk, int E, int32_t *sorted_e, int32_t *sorted_s,
+                 int32_t *offsets, void *ws) {
+  int nchunk = ceil_div(Tk > 0 ? Tk : 1, ROUTE_CHUNK);
+  int32_t *counts = (int32_t *)ws;
+  size_t shm = (size_t)E * sizeof(int32_t);
+  hipLaunchKernelGGL(route_count_kernel, dim3(nchunk), dim3(64), shm, s, expert_idxs, Tk, E, counts);
+  SMOE_LAUNCH_CHECK();
+  hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(256), shm, s, counts, nchunk, E, offsets, Tk);
+  SMOE_LAUNCH_CHECK();
+  if (Tk > 0) {
+    hipLaunchKernelGGL(route_place_kernel, dim3(nchunk), dim3(64), shm, s, expert_idxs, Tk, E, counts, sorted_e,
+                       sorted_s);
+    SMOE_LAUNCH_CHECK();
+  }
+  return SMOE_OK;
+}

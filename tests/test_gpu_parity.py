@@ -1,0 +1,249 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle on the same seeded inputs.
+
+Bar: bit-exact for routing indices and offsets; max |gpu - ref| / max |ref| <= 1e-5 (fp32)
+or 2e-2 (bf16 inputs, fp32 accumulation) per tensor for outputs and gradients; gates at
+1e-6 absolute.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import smoe_inputs as si
+from helpers import TOL, assert_close, dev, oracle_routing, rel_err, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def smoe():
+    import paper_2403_08245_amd as m
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    m.ctx()
+    return m
+
+
+def _log(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------------ routing (bit-exact)
+ROUTING_CASES = [
+    (1, 1, 1), (3, 4, 4), (64, 64, 8), (4, 64, 8), (256, 4, 2), (1000, 7, 3), (1023, 8, 1),
+    (1025, 8, 2), (16384, 8, 2), (8192, 64, 8), (5000, 130, 5), (777, 1, 1),
+]
+
+
+@pytest.mark.parametrize("T,E,k", ROUTING_CASES)
+def test_topk_and_route_bit_exact(smoe, T, E, k):
+    _log(f"routing T={T} E={E} k={k}")
+    logits = torch.randn(T, E, generator=torch.Generator().manual_seed(T * 131 + E), dtype=torch.float32)
+    ei, g, se, o, off = oracle_routing(logits, k, E)
+    gi, gg = smoe.topk_gate(logits.cuda(), k)
+    assert np.array_equal(gi.cpu().numpy(), ei)
+    assert np.abs(gg.cpu().numpy().astype(np.float64) - g).max() <= 1e-6
+    r = smoe.route(gi, E)
+    assert np.array_equal(r.sorted_expert_idxs.cpu().numpy(), se)
+    assert np.array_equal(r.sorted_scattered_idxs.cpu().numpy(), o)
+    assert np.array_equal(r.expert_offsets.cpu().numpy(), off)
+
+
+def test_topk_ties_and_quantised_logits(smoe):
+    g = torch.Generator().manual_seed(5)
+    logits = torch.randint(-2, 3, (2048, 16), generator=g).to(torch.float32)     # many exact ties
+    ei, gates, se, o, off = oracle_routing(logits, 4, 16)
+    gi, gg = smoe.topk_gate(logits.cuda(), 4)
+    assert np.array_equal(gi.cpu().numpy(), ei)
+    assert np.abs(gg.cpu().numpy() - gates).max() <= 1e-6
+
+
+@pytest.mark.parametrize("pattern", ["one_expert", "empty_middle", "k_equals_E", "masked"])
+def test_route_degenerate_distributions(smoe, pattern):
+    T, E, k = 300, 8, 2
+    if pattern == "one_expert":
+        ei = np.full((T, 1), 5, dtype=np.int32); k = 1
+    elif pattern == "empty_middle":
+        ei = np.stack([np.zeros(T), np.full(T, 7)], 1).astype(np.int32)
+    elif pattern == "k_equals_E":
+        k = E
+        ei = np.stack([np.random.default_rng(t).permutation(E) for t in range(T)]).astype(np.int32)
+    else:
+        cfg = si.CONFIGS["C4-decode-masked"]
+        logits = si.router_logits(cfg, 3)
+        ei, _ = oracle.topk_gate(logits.numpy(), cfg.k)
+        E = cfg.E
+        assert (np.bincount(ei.reshape(-1), minlength=E) == 0).sum() >= 16
+    se, o, off = oracle.route(ei, E)
+    r = smoe.route(dev(ei), E)
+    assert np.array_equal(r.sorted_expert_idxs.cpu().numpy(), se)
+    assert np.array_equal(r.sorted_scattered_idxs.cpu().numpy(), o)
+    assert np.array_equal(r.expert_offsets.cpu().numpy(), off)
+
+
+def test_route_empty_input(smoe):
+    r = smoe.route(torch.empty(0, 2, dtype=torch.int32, device="cuda"), 4)
+    assert r.expert_offsets.cpu().tolist() == [0, 0, 0, 0, 0]
+
+
+# ------------------------------------------------------------------ ParallelLinear
+def _plinear_setup(smoe, T, d_in, d_out, E, k, dtype, seed, grouped_in):
+    x_rows = T * k if grouped_in else T
+    c = si.plinear_case(T, d_in, d_out, E, k, dtype, seed, x_rows=x_rows)
+    ei, g, se, o, off = oracle_routing(c["logits"], k, E)
+    gi, gg = smoe.topk_gate(c["logits"].cuda(), k)
+    r = smoe.route(gi, E)
+    return c, (ei, g, se, o, off), (gi, gg, r)
+
+
+PL_SHAPES = [
+    # T, d_in, d_out, E, k   (several tiles, ragged tails, more experts than rows)
+    (96, 64, 128, 4, 2),
+    (333, 72, 40, 5, 3),
+    (7, 16, 24, 16, 2),
+    (520, 256, 136, 3, 1),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("gin,gout,with_p", [(0, 0, 0), (0, 1, 0), (1, 0, 0), (1, 1, 0), (0, 0, 1), (1, 0, 1)])
+@pytest.mark.parametrize("shape", PL_SHAPES)
+def test_plinear_forward_and_backward(smoe, shape, gin, gout, with_p, dtype):
+    T, d_in, d_out, E, k = shape
+    _log(f"plinear shape={shape} gin={gin} gout={gout} p={with_p} {dtype}")
+    td = torch_dtype(dtype)
+    c, (ei, g, se, o, off), (gi, gg, r) = _plinear_setup(smoe, T, d_in, d_out, E, k, dtype, 7, gin)
+    fan = 1 if gin else k
+    X, W = si.as_f64(c["X"]), si.as_f64(c["W"])
+    p64 = gg.cpu().numpy().astype(np.float64) if with_p else None       # the f32 gates the GPU uses
+    Y_ref, Yhat_ref = oracle.plinear_fwd(X, W, se, o, fan, p64, bool(gin), bool(gout))
+    Y, Yhat = smoe.plinear_fwd(c["X"].cuda(), c["W"].cuda(), r, fan, gg if with_p else None, bool(gin), bool(gout))
+    assert_close(Yhat, Yhat_ref, td, "Yhat")
+    assert_close(Y, Y_ref, td, "Y")
+    dY_t = c["dY_T"] if with_p else c["dY_Tk"]
+    dX_ref, dW_ref, dp_ref = oracle.plinear_bwd(si.as_f64(dY_t), X, W, se, o, fan, p64, bool(gin), bool(gout))
+    dX, dW, dg = smoe.plinear_bwd(dY_t.cuda(), c["X"].cuda(), c["W"].cuda(), Yhat, r, fan,
+                                  gg if with_p else None, bool(gin), bool(gout))
+    assert_close(dX, dX_ref, td, "dX")
+    assert_close(dW, dW_ref, td, "dW")
+    if with_p:
+        assert_close(dg, dp_ref, td, "dgates")
+
+
+def test_group_matches_definition(smoe):
+    c, (ei, g, se, o, off), (gi, gg, r) = _plinear_setup(smoe, 200, 64, 64, 6, 2, "bf16", 3, 0)
+    out = smoe.group(c["X"].cuda(), r, 2)
+    assert torch.equal(out.cpu(), c["X"][torch.from_numpy(o.astype(np.int64)) // 2])
+    outw = smoe.group(c["dY_T"].cuda(), r, 2, gg)
+    ref = g.reshape(-1)[o][:, None] * si.as_f64(c["dY_T"])[o // 2]
+    assert_close(outw, ref, torch.bfloat16, "weighted group")
+
+
+# ------------------------------------------------------------------ SMoE MLP, whole-tensor parity
+def _mlp_parity(smoe, cfg, seed, plain=False):
+    td = torch_dtype(cfg.dtype)
+    case = si.mlp_case(cfg, seed)
+    smoe.set_kernel_mode(1 if plain else 0)
+    try:
+        gi, gg = smoe.topk_gate(case["logits"].cuda(), cfg.k)
+        r = smoe.route(gi, cfg.E)
+        ei, g, se, o, off = oracle_routing(case["logits"], cfg.k, cfg.E)
+        assert np.array_equal(gi.cpu().numpy(), ei)
+        assert np.array_equal(r.sorted_scattered_idxs.cpu().numpy(), o)
+        assert np.array_equal(r.expert_offsets.cpu().numpy(), off)
+        X, W1, W2, dYc = (case[n].cuda() for n in ("X", "W1", "W2", "dY"))
+        Y, buf = smoe.mlp_fwd(X, W1, W2, r, cfg.k, gg, cfg.act)
+        dX, dW1, dW2, dg = smoe.mlp_bwd(dYc, X, W1, W2, r, cfg.k, gg, cfg.act, buf)
+        torch.cuda.synchronize()
+    finally:
+        smoe.set_kernel_mode(0)
+    g64 = gg.cpu().numpy().astype(np.float64)
+    X64, W164, W264, dY64 = (si.as_f64(case[n]) for n in ("X", "W1", "W2", "dY"))
+    ref = oracle.mlp_fwd(X64, W164, W264, ei, g64, cfg.act)
+    errs = {}
+    errs["Y"] = assert_close(Y, ref["Y"], td, "Y")
+    errs["Hpre"] = assert_close(buf.Hpre, ref["Hpre"][o], td, "Hpre (grouped)")
+    errs["H"] = assert_close(buf.H, ref["H"][o], td, "H (grouped)")
+    errs["Yhat"] = assert_close(buf.Yhat, ref["Yhat"], td, "Yhat (scattered)")
+    gref = oracle.mlp_bwd(dY64, X64, W164, W264, ei, g64, cfg.act)
+    errs["dX"] = assert_close(dX, gref["dX"], td, "dX")
+    errs["dW1"] = assert_close(dW1, gref["dW1"], td, "dW1")
+    errs["dW2"] = assert_close(dW2, gref["dW2"], td, "dW2")
+    errs["dgates"] = assert_close(dg, gref["dgates"], td, "dgates")
+    _log(cfg.name, {k: f"{v:.2e}" for k, v in errs.items()})
+    return case, (X, W1, W2, dYc, r, gg)
+
+
+def test_mlp_C1_fp32_full(smoe):
+    _mlp_parity(smoe, si.CONFIGS["C1"], 0)
+
+
+@pytest.mark.parametrize("name", ["C3-small", "C3-small-f32"])
+def test_mlp_reduced_mixtral_shape_full(smoe, name):
+    _mlp_parity(smoe, si.CONFIGS[name], 1)
+
+
+def test_mlp_bf16_plain_kernels_full(smoe):
+    _mlp_parity(smoe, si.CONFIGS["C3-small"], 2, plain=True)
+
+
+@pytest.mark.parametrize("act", [si.ACT_NONE, si.ACT_GELU, si.ACT_SWIGLU])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_mlp_ragged_shapes_with_empty_experts(smoe, act, dtype):
+    # T*k < E rows for some experts, widths that are not multiples of the GEMM tiles
+    cfg = si.custom("ragged", T=37, d_model=72, d_expert=40, E=12, k=3, act=act, dtype=dtype, masked_experts=4)
+    _mlp_parity(smoe, cfg, 4)
+
+
+def test_mlp_k1_and_k_equals_E(smoe):
+    _mlp_parity(smoe, si.custom("k1", T=130, d_model=64, d_expert=64, E=4, k=1, act=si.ACT_SWIGLU, dtype="bf16"), 5)
+    _mlp_parity(smoe, si.custom("kE", T=50, d_model=64, d_expert=32, E=4, k=4, act=si.ACT_GELU, dtype="f32"), 6)
+
+
+def test_mlp_is_deterministic(smoe):
+    cfg = si.CONFIGS["C3-small"]
+    case, (X, W1, W2, dYc, r, gg) = _mlp_parity(smoe, cfg, 9)
+    outs = []
+    for _ in range(2):
+        Y, buf = smoe.mlp_fwd(X, W1, W2, r, cfg.k, gg, cfg.act)
+        g = smoe.mlp_bwd(dYc, X, W1, W2, r, cfg.k, gg, cfg.act, buf)
+        outs.append([t.clone() for t in (Y,) + tuple(g)])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+def test_mlp_inference_mode_and_empty_batch(smoe):
+    cfg = si.CONFIGS["C1"]
+    case = si.mlp_case(cfg, 0)
+    gi, gg = smoe.topk_gate(case["logits"].cuda(), cfg.k)
+    r = smoe.route(gi, cfg.E)
+    X, W1, W2 = (case[n].cuda() for n in ("X", "W1", "W2"))
+    Yt, _ = smoe.mlp_fwd(X, W1, W2, r, cfg.k, gg, cfg.act, training=True)
+    Yi, _ = smoe.mlp_fwd(X, W1, W2, r, cfg.k, gg, cfg.act, training=False)
+    assert torch.equal(Yt, Yi)
+    # T = 0: nothing to do, weight gradients are zeros
+    e = torch.empty(0, cfg.k, dtype=torch.int32, device="cuda")
+    r0 = smoe.route(e, cfg.E)
+    X0 = torch.empty(0, cfg.d_model, device="cuda")
+    g0 = torch.empty(0, cfg.k, device="cuda")
+    Y0, buf0 = smoe.mlp_fwd(X0, W1, W2, r0, cfg.k, g0, cfg.act)
+    buf0.dW1.fill_(7.0); buf0.dW2.fill_(7.0)
+    dX0, dW1, dW2, dg0 = smoe.mlp_bwd(X0, X0, W1, W2, r0, cfg.k, g0, cfg.act, buf0)
+    assert Y0.shape[0] == 0 and float(dW1.abs().max()) == 0.0 and float(dW2.abs().max()) == 0.0
+
+
+def test_error_codes(smoe):
+    cfg = si.CONFIGS["C1"]
+    case = si.mlp_case(cfg, 0)
+    gi, gg = smoe.topk_gate(case["logits"].cuda(), cfg.k)
+    r = smoe.route(gi, cfg.E)
+    X, W1 = case["X"].cuda(), case["W1"].cuda()
+    with pytest.raises(smoe.SmoeError, match="invalid"):
+        smoe.topk_gate(case["logits"].cuda(), cfg.E + 1)
+    with pytest.raises(smoe.SmoeError, match="invalid"):
+        smoe.plinear_fwd(X, W1, r, cfg.k + 1)                       # fan-out does not match Tk
+    with pytest.raises(smoe.SmoeError, match="invalid"):
+        smoe.plinear_fwd(X, W1, r, cfg.k, gg, False, True)          # gates need scattered output
+    Xodd = torch.zeros(cfg.T, 66, device="cuda")
+    Wodd = torch.zeros(cfg.E, 66, 66, device="cuda")
+    with pytest.raises(smoe.SmoeError, match="unsupported"):
+        smoe.plinear_fwd(Xodd, Wodd, r, cfg.k)                      # width not a multiple of 16 bytes
