@@ -1,0 +1,171 @@
+#!/usr/bin/env python3
+"""Benchmark of the SMoE MLP hot path (routing + Alg. 3 forward + backward) on one MI355X.
+
+One "step" = top-k gate, routing sort, SMoE MLP forward and backward over one synthetic
+batch that is already resident in HBM.  Prints ONE JSON line:
+  metric/value  GEMM TFLOP/s of fwd+bwd (6 grouped GEMMs, 2*Tk*d_model*(d_h+d_expert)*3 flop)
+  roofline      the dominant kernel (scatter2scatter of the first ParallelLinear) timed alone
+                with HIP events against the dense bf16 MFMA peak
+  cpu_baseline  the fp64 CPU oracle timed on a few sampled tokens of the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak (published)
+PEAK_FP32_TFLOPS = 157.3
+
+
+def _events(n):
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def cpu_baseline(case, cfg, gates_np, ei_np, budget_s: float):
+    """Times the oracle's per-token forward+backward on sampled tokens (bounded CPU work)."""
+    import oracle
+    import smoe_inputs as si
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    X = si.as_f32(case["X"]); dY = si.as_f32(case["dY"])
+    W1 = si.as_f32(case["W1"]); W2 = si.as_f32(case["W2"])
+    rng = np.random.default_rng(0)
+    order = rng.permutation(cfg.T)
+    t0 = time.perf_counter()
+    n = 0
+    for t in order:
+        oracle.mlp_token_fwd(X[t], ei_np[t], gates_np[t], W1, W2, cfg.act)
+        oracle.mlp_token_bwd(X[t], dY[t], ei_np[t], gates_np[t], W1, W2, cfg.act)
+        n += 1
+        if time.perf_counter() - t0 > budget_s or n >= 4096:
+            break
+    dt = time.perf_counter() - t0
+    flops_per_token = 3.0 * cfg.gemm_flops_fwd() / cfg.T
+    return {
+        "value": n * flops_per_token / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+        "tokens_per_s": n / dt,
+        "sample": f"{n} randomly sampled tokens of {cfg.name}: per-token fp64 forward + analytic backward "
+                  f"(activation/input gradients; weight-gradient outer products not formed), {dt:.1f} s",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the oracle baseline (0 = skip)")
+    ap.add_argument("--kernel-reps", type=int, default=20)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (data-parallel sharding is a design note); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import smoe_inputs as si
+    import paper_2403_08245_amd as smoe
+
+    cfg = si.CONFIGS[args.workload]
+    td = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    case = si.mlp_case(cfg, args.seed)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    logits, X, W1, W2, dY = (case[n].to(dev) for n in ("logits", "X", "W1", "W2", "dY"))
+    buf = smoe.MLPBuffers(cfg.T, cfg.k, cfg.E, cfg.d_model, cfg.d_expert, cfg.act, td, dev, training=True)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        ei, gates = smoe.topk_gate(logits, cfg.k)
+        r = smoe.route(ei, cfg.E)
+        smoe.mlp_fwd(X, W1, W2, r, cfg.k, gates, cfg.act, buf)
+        smoe.mlp_bwd(dY, X, W1, W2, r, cfg.k, gates, cfg.act, buf)
+        return ei, gates, r
+
+    for _ in range(args.warmup):
+        ei, gates, r = step()
+    torch.cuda.synchronize()
+    ev = _events(args.steps + 1)
+    t0 = time.perf_counter()
+    ev[0].record(stream)
+    for i in range(args.steps):
+        step()
+        ev[i + 1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_step = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)])
+    ms = wall * 1e3 / args.steps
+
+    flops = 3.0 * cfg.gemm_flops_fwd()
+    tflops = flops / (ms * 1e-3) / 1e12
+    peak = PEAK_BF16_TFLOPS if cfg.dtype == "bf16" else PEAK_FP32_TFLOPS
+
+    # phases, each timed with events on the launch stream
+    def timed(fn, reps):
+        fn(); torch.cuda.synchronize()
+        e = _events(2)
+        e[0].record(stream)
+        for _ in range(reps):
+            fn()
+        e[1].record(stream)
+        torch.cuda.synchronize()
+        return e[0].elapsed_time(e[1]) / reps
+
+    reps = args.kernel_reps
+    ms_route = timed(lambda: smoe.route(smoe.topk_gate(logits, cfg.k)[0], cfg.E), reps)
+    ms_fwd = timed(lambda: smoe.mlp_fwd(X, W1, W2, r, cfg.k, gates, cfg.act, buf), reps)
+    ms_bwd = timed(lambda: smoe.mlp_bwd(dY, X, W1, W2, r, cfg.k, gates, cfg.act, buf), reps)
+
+    # dominant kernel: scatter2scatter of the first ParallelLinear (scattered -> grouped), one launch per call
+    import ctypes
+    rc = r.c()
+    d_h = cfg.d_h
+    dt_code = smoe.BF16 if cfg.dtype == "bf16" else smoe.F32
+
+    def s2s_once():
+        smoe._check(smoe.lib.smoe_plinear_fwd(smoe.ctx(), stream.cuda_stream, dt_code, X.data_ptr(), cfg.T, cfg.d_model,
+                                              W1.data_ptr(), d_h, ctypes.byref(rc), cfg.k, None, 0, 0, 1,
+                                              buf.Hpre.data_ptr(), None), "smoe_plinear_fwd")
+
+    ms_s2s = timed(s2s_once, reps)
+    s2s_flops = 2.0 * cfg.Tk * cfg.d_model * d_h
+    achieved = s2s_flops / (ms_s2s * 1e-3) / 1e12
+
+    out = {
+        "metric": "SMoE MLP fwd+bwd GEMM throughput per layer (routing + Alg. 3 forward + backward)",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: T={cfg.T} d_model={cfg.d_model} d_expert={cfg.d_expert} E={cfg.E} "
+                               f"k={cfg.k} act={'swiglu' if cfg.act == 2 else 'gelu'} zipf_s={cfg.zipf_s}",
+                   "global_batch": cfg.T, "expert_rows": np.diff(r.expert_offsets.cpu().numpy()).tolist()},
+        "tokens_per_s": cfg.T / (ms * 1e-3),
+        "frac_mfma_peak": tflops / peak,
+        "ms_event_median": float(np.median(per_step)), "ms_event_p5": float(np.percentile(per_step, 5)),
+        "ms_event_p95": float(np.percentile(per_step, 95)),
+        "phases_ms": {"routing": ms_route, "mlp_fwd": ms_fwd, "mlp_bwd": ms_bwd},
+        "roofline": {"bound": "mfma", "kernel": "s2s_mfma_kernel (ParallelLinear #1, scattered->grouped)",
+                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                     "ms_per_launch": ms_s2s, "flop_per_launch": s2s_flops, "traffic": None},
+    }
+    if args.cpu_seconds > 0:
+        out["cpu_baseline"] = cpu_baseline(case, cfg, gates.cpu().numpy().astype(np.float64), ei.cpu().numpy(),
+                                           args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
