@@ -93,6 +93,20 @@ template <int C> __device__ __forceinline__ bf16x8 tr_frag(const char *tile, int
   return u.v;
 }
 
+
+// Pins the instruction order of one contraction sub-step: every matrix instruction is
+// followed by one LDS read of the next sub-step's fragments, so the reads complete under the
+// shadow of the MFMA pipe instead of after it (one wavefront per SIMD has nothing else to
+// hide them behind).
+template <int N_MFMA, int N_DSREAD> __device__ __forceinline__ void interleave_mfma_dsread() {
+#pragma unroll
+  for (int i = 0; i < N_DSREAD; ++i) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 DS read
+  }
+  if (N_MFMA > N_DSREAD) __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA - N_DSREAD, 0);
+}
+
 // Finds expert and first row of M-tile `tile` when each expert's segment is cut into BM-row tiles.
 __device__ __forceinline__ bool locate_tile(const int32_t *offsets, int E, int bm, int tile, int &e, int &row0,
                                             int &row_end) {
@@ -236,6 +250,7 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_mfma_kernel(S2SArgs a, int ti
 #pragma unroll
         for (int j = 0; j < FN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
+      if (kk + 1 < BK / 16) interleave_mfma_dsread<FM * FN, FM + (TRANS_W ? FN : 2 * FN)>();
     }
   }
   store_tile_rows<BM, BN, FM, FN>(acc, (bf16_t *)a.C, a.N, a.c_map, row0, row_end, n0, a.N, wm, wn, lane);
@@ -250,8 +265,15 @@ __global__ void __launch_bounds__(NTHREADS, 1) dw_mfma_kernel(DWArgs a, int tile
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   __shared__ int s_expert;
+  // Ring of source-row numbers, [slot][operand][row of the step]; -1 marks rows past the segment.
+  // The numbers of step s are fetched from the routing arrays two steps early by 128 threads,
+  // parked in a register, and published here one step early, so the gathered global->LDS
+  // loads never wait on an index lookup.
+  __shared__ int s_idx[4][2][BK];
 
-  const int vid = xcd_contiguous_id(blockIdx.x, gridDim.x);
+  // Block ids map to tiles directly: consecutive blocks (dealt round-robin to the XCDs) share
+  // an expert, so every XCD gets the same mix of long and short contractions.
+  const int vid = blockIdx.x;
   const int per_expert = tiles_m * tiles_n;
   const int rank = vid / per_expert;
   if (rank >= a.E) return;
@@ -269,6 +291,7 @@ __global__ void __launch_bounds__(NTHREADS, 1) dw_mfma_kernel(DWArgs a, int tile
   const int t = vid % per_expert;
   const int m0 = (t % tiles_m) * BM, n0 = (t / tiles_m) * BN;
   const int lo = a.offsets[e], hi = a.offsets[e + 1];
+  const int nsteps = (hi - lo + BK - 1) / BK;
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;
@@ -291,20 +314,26 @@ __global__ void __launch_bounds__(NTHREADS, 1) dw_mfma_kernel(DWArgs a, int tile
     cb[I] = n0 + c * 8;
     if (cb[I] >= a.N) cb[I] = 0;
   }
-  // source pointers of one step: token rows come through the routing maps, rows past the
-  // segment read a block of zeros so they add nothing to the sum
+  const int irow = threadIdx.x & 63, iop = threadIdx.x >> 6;  // waves 0/1 look up rows of A/B
+  auto lookup = [&](int ks) -> int {
+    int i = lo + ks * BK + irow;
+    if (iop >= 2 || i >= hi) return -1;
+    return iop == 0 ? map_row(a.a_map, i) : map_row(a.b_map, i);
+  };
+  // source pointers of one step; rows past the segment read a block of zeros so they add
+  // nothing to the sum
   const bf16_t *pa[BM / 32], *pb[BN / 32];
   auto resolve = [&](int ks) {
-    int i0 = lo + ks * BK;
+    const int slot = ks & 3;
 #pragma unroll
     for (int I = 0; I < BM / 32; ++I) {
-      int i = i0 + ra[I];
-      pa[I] = (i < hi) ? A + (size_t)map_row(a.a_map, i) * a.M + ca[I] : (const bf16_t *)g_zero16;
+      int row = s_idx[slot][0][ra[I]];
+      pa[I] = (row >= 0) ? A + (size_t)row * a.M + ca[I] : (const bf16_t *)g_zero16;
     }
 #pragma unroll
     for (int I = 0; I < BN / 32; ++I) {
-      int i = i0 + rb[I];
-      pb[I] = (i < hi) ? B + (size_t)map_row(a.b_map, i) * a.N + cb[I] : (const bf16_t *)g_zero16;
+      int row = s_idx[slot][1][rb[I]];
+      pb[I] = (row >= 0) ? B + (size_t)row * a.N + cb[I] : (const bf16_t *)g_zero16;
     }
   };
   const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
@@ -332,22 +361,28 @@ __global__ void __launch_bounds__(NTHREADS, 1) dw_mfma_kernel(DWArgs a, int tile
 #pragma unroll
       for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
 
-  const int nsteps = (hi - lo + BK - 1) / BK;
+  if (threadIdx.x < 128) {
+    s_idx[0][iop][irow] = lookup(0);
+    s_idx[1][iop][irow] = lookup(1);
+  }
+  int parked = lookup(2);
+  __syncthreads();
   if (nsteps > 0) {
     resolve(0);
     issue(0);
-    if (nsteps > 1) resolve(1);
   }
   for (int ks = 0; ks < nsteps; ++ks) {
     wait_all_loads();
+    if (threadIdx.x < 128) s_idx[(ks + 2) & 3][iop][irow] = parked;
     __syncthreads();
     const char *at = smem + (ks & 1) * STAGE;
     bf16x8 fa[2][FM], fb[2][FN];
     frags(at, 0, fa[0], fb[0]);
     if (ks + 1 < nsteps) {
+      resolve(ks + 1);
       issue((ks + 1) & 1);
-      if (ks + 2 < nsteps) resolve(ks + 2);   // index lookups for the step after next, off the critical path
     }
+    parked = lookup(ks + 3);
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       if (kk + 1 < BK / 16) frags(at, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
@@ -356,6 +391,7 @@ __global__ void __launch_bounds__(NTHREADS, 1) dw_mfma_kernel(DWArgs a, int tile
 #pragma unroll
         for (int j = 0; j < FN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
+      if (kk + 1 < BK / 16) interleave_mfma_dsread<FM * FN, 2 * FM + 2 * FN>();
     }
   }
   bf16_t *dW = (bf16_t *)a.dW + (size_t)e * a.M * a.N;
