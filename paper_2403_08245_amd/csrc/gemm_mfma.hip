@@ -6,16 +6,20 @@
 //   * groupXTY (Sec. 3.2.1): dW[e] = Xbar_e^T dYbar_e over the expert's variable-length row
 //     segment, the token rows again gathered on the fly.
 //
-// Shape of every kernel: 256 threads = 4 wavefronts in a 2x2 grid over a BM x BN output
-// tile, v_mfma_f32_32x32x16_bf16 with fp32 accumulators, contraction step 64, two LDS
-// stages filled by direct-to-LDS 16-byte global loads (each lane supplies its own gathered
-// address), one barrier per step.
+// Shape of every kernel: 256 threads = 4 wavefronts in a 2x2 grid over a 256x256 output tile
+// (one wavefront per SIMD, 256 fp32 accumulator registers each), v_mfma_f32_32x32x16_bf16.
+// The contraction runs in half-steps of 32 elements through a ring of four 32 KB LDS stages
+// filled by direct-to-LDS 16-byte global loads (each lane supplies its own gathered address):
+// while stage h is multiplied, stage h+1 has landed (its first fragments are prefetched across
+// the barrier), stage h+2 is in flight and stage h+3 is being requested, one load instruction
+// per four MFMAs so that neither the texture path nor the LDS ever sees a burst.  One barrier
+// per half-step; the matrix pipe has its next operands in registers when it is released.
 //
 // Two LDS tile layouts, both XOR-swizzled at 16-byte granularity so that the fragment reads
 // are bank-conflict free:
-//   KC tile: rows x 64 contraction elements, contraction contiguous (128 B per row); a lane's
+//   KC tile: rows x 32 contraction elements, contraction contiguous (64 B per row); a lane's
 //            8 consecutive-k fragment comes from one ds_read_b128.
-//   TR tile: 64 contraction rows x C columns, columns contiguous; fragments come from two
+//   TR tile: 32 contraction rows x 256 columns, columns contiguous; fragments come from two
 //            ds_read_b64_tr_b16 (the transposing LDS read), which hand each lane 4
 //            consecutive contraction elements of one column.
 // Forward uses KC for X and TR for W; the input gradient uses KC for both (W^T is already
@@ -29,85 +33,74 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int BK = 64;            // contraction elements per step
+constexpr int HK = 32;            // contraction elements per LDS stage (one half-step)
+constexpr int NSTAGE = 4;
 constexpr int NTHREADS = 256;
-constexpr int NWAVES = 4;
+constexpr int TB = 256;           // tile edge (rows and columns of the output tile)
+constexpr int TILE_BYTES = TB * HK * 2;       // one operand tile of one stage: 16 KB
+constexpr int STAGE_BYTES = 2 * TILE_BYTES;   // A tile then B tile
+constexpr int NLD = TB / 64;      // load instructions per wavefront per operand tile (4)
+constexpr int FR = TB / 64;       // 32x32 fragments per wavefront along each tile edge (4)
 
 #define LDS_AS __attribute__((address_space(3)))
-#define GLB_AS __attribute__((address_space(1)))
 
-// 16 bytes per lane, global -> LDS without passing through registers.  The LDS destination
-// (a byte address in M0) is wave-uniform; lane L's data lands at lds_addr + 16 * L.  Written
-// as inline assembly so that the waits are placed by hand: the loads of the next stage stay in
-// flight while the current stage is read, and only `wait_all_loads` + the barrier order them.
+// 16 (or 4) bytes per lane, global -> LDS without passing through registers.  The LDS
+// destination (a byte address in M0) is wave-uniform; lane L's data lands at lds_addr +
+// 16 * L (4 * L).  Written as inline assembly so that the waits are placed by hand: several
+// stages stay in flight while another one is read, ordered only by `wait_loads` + barrier.
 __device__ __forceinline__ void load16_to_lds(const void *gsrc, uint32_t lds_addr) {
   __asm__ volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gsrc) : "memory", "m0");
 }
-__device__ __forceinline__ void wait_all_loads() { __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+__device__ __forceinline__ void load4_to_lds(const void *gsrc, uint32_t lds_addr) {
+  __asm__ volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(gsrc) : "memory", "m0");
+}
+// Waits until at most N of this wavefront's global loads are outstanding (they finish in order).
+template <int N> __device__ __forceinline__ void wait_loads() {
+  __asm__ volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 __device__ __forceinline__ uint32_t lds_address(const char *p) { return (uint32_t)(size_t)(LDS_AS const char *)p; }
+__device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
 
 __device__ __align__(16) const uint32_t g_zero16[4] = {0u, 0u, 0u, 0u};
 
-// ---------------------------------------------------------------- KC tile (rows x 64, k contiguous)
-__device__ __forceinline__ int kc_swz(int row) { return (row >> 1) & 7; }
-// lane's source chunk for load instruction `inst` of a ROWS-row tile: returns the tile row and
-// the logical 16-byte chunk (0..7) this lane must fetch so that LDS ends up swizzled.
-template <int ROWS>
+// ---------------------------------------------------------------- KC tile (256 rows x 32, k contiguous)
+__device__ __forceinline__ int kc_swz(int row) { return (row >> 2) & 3; }
+// Load instruction `inst` (0..3) of a wavefront covers 16 rows; lane -> (tile row, source chunk).
 __device__ __forceinline__ void kc_lane_slot(int wave, int lane, int inst, int &row, int &chunk) {
-  row = (wave * (ROWS / 32) + inst) * 8 + (lane >> 3);
-  chunk = (lane & 7) ^ kc_swz(row);
-}
-template <int ROWS> __device__ __forceinline__ int kc_inst_off(int wave, int inst) {
-  return (wave * (ROWS / 32) + inst) * 1024;
+  row = (wave * NLD + inst) * 16 + (lane >> 2);
+  chunk = (lane & 3) ^ kc_swz(row);
 }
 // fragment for v_mfma_32x32x16: lane holds row (rbase + lane%32), k = kk*16 + 8*(lane/32) + 0..7
 __device__ __forceinline__ bf16x8 kc_frag(const char *tile, int rbase, int kk, int lane) {
   int row = rbase + (lane & 31);
   int chunk = (kk * 2 + (lane >> 5)) ^ kc_swz(row);
-  return *reinterpret_cast<const bf16x8 *>(tile + row * 128 + chunk * 16);
+  return *reinterpret_cast<const bf16x8 *>(tile + row * 64 + chunk * 16);
 }
 
-// ---------------------------------------------------------------- TR tile (64 x C, columns contiguous)
+// ---------------------------------------------------------------- TR tile (32 x 256, columns contiguous)
 __device__ __forceinline__ int tr_swz(int row) { return (row & 3) << 2; }
-template <int C>
+// Load instruction `inst` (0..3) of a wavefront covers 2 contraction rows of 512 B.
 __device__ __forceinline__ void tr_lane_slot(int wave, int lane, int inst, int &row, int &chunk) {
-  constexpr int CPR = C / 8;          // 16-byte chunks per row
-  constexpr int RPI = 64 / CPR;       // rows per load instruction
-  row = (wave * (C / 32) + inst) * RPI + lane / CPR;
-  chunk = (lane % CPR) ^ tr_swz(row);
-}
-template <int C> __device__ __forceinline__ int tr_inst_off(int wave, int inst) {
-  return (wave * (C / 32) + inst) * 1024;
+  row = (wave * NLD + inst) * 2 + (lane >> 5);
+  chunk = (lane & 31) ^ tr_swz(row);
 }
 // fragment: lane holds column (cbase + lane%32), contraction rows kk*16 + 8*(lane/32) + 0..7
-template <int C> __device__ __forceinline__ bf16x8 tr_frag(const char *tile, int cbase, int kk, int lane) {
+__device__ __forceinline__ bf16x8 tr_frag(const char *tile, int cbase, int kk, int lane) {
   int col = cbase + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
   int row0 = kk * 16 + 8 * (lane >> 5) + ((lane & 15) >> 2);
   union { bf16x8 v; s16x4 h[2]; } u;
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
     int row = row0 + 4 * t;
-    int off = row * (C * 2) + ((((col >> 3) ^ tr_swz(row))) << 4) + ((col & 7) << 1);
+    int off = row * (TB * 2) + ((((col >> 3) ^ tr_swz(row))) << 4) + ((col & 7) << 1);
     u.h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4 *)(tile + off));
   }
   return u.v;
 }
+// byte offset inside an operand tile of a wavefront's load instruction (both layouts: 1 KB each)
+__device__ __forceinline__ int inst_off(int wave, int inst) { return (wave * NLD + inst) * 1024; }
 
-
-// Pins the instruction order of one contraction sub-step: every matrix instruction is
-// followed by one LDS read of the next sub-step's fragments, so the reads complete under the
-// shadow of the MFMA pipe instead of after it (one wavefront per SIMD has nothing else to
-// hide them behind).
-template <int N_MFMA, int N_DSREAD> __device__ __forceinline__ void interleave_mfma_dsread() {
-#pragma unroll
-  for (int i = 0; i < N_DSREAD; ++i) {
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
-    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 DS read
-  }
-  if (N_MFMA > N_DSREAD) __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA - N_DSREAD, 0);
-}
-
-// Finds expert and first row of M-tile `tile` when each expert's segment is cut into BM-row tiles.
+// Finds expert and first row of M-tile `tile` when each expert's segment is cut into bm-row tiles.
 __device__ __forceinline__ bool locate_tile(const int32_t *offsets, int E, int bm, int tile, int &e, int &row0,
                                             int &row_end) {
   int acc = 0;
@@ -132,19 +125,18 @@ __device__ __forceinline__ int xcd_contiguous_id(int pid, int grid) {
   return (pid & 7) * per + (pid >> 3);
 }
 
-template <int BM, int BN, int FM, int FN>
-__device__ __forceinline__ void store_tile_rows(const f32x16 (&acc)[FM][FN], bf16_t *C, int ldc, const RowMap &cmap,
+__device__ __forceinline__ void store_tile_rows(const f32x16 (&acc)[FR][FR], bf16_t *C, int ldc, const RowMap &cmap,
                                                 int row0, int row_end, int col0, int ncols, int wm, int wn, int lane) {
 #pragma unroll
-  for (int fm = 0; fm < FM; ++fm) {
-    int i = row0 + wm * (BM / 2) + fm * 32 + (lane & 31);
+  for (int fm = 0; fm < FR; ++fm) {
+    int i = row0 + wm * (TB / 2) + fm * 32 + (lane & 31);
     if (i >= row_end) continue;
     bf16_t *crow = C + (size_t)map_row(cmap, i) * ldc;
 #pragma unroll
-    for (int fn = 0; fn < FN; ++fn) {
+    for (int fn = 0; fn < FR; ++fn) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        int n = col0 + wn * (BN / 2) + fn * 32 + 8 * g + 4 * (lane >> 5);
+        int n = col0 + wn * (TB / 2) + fn * 32 + 8 * g + 4 * (lane >> 5);
         if (n < ncols) {
           bf16x4 v;
 #pragma unroll
@@ -156,13 +148,119 @@ __device__ __forceinline__ void store_tile_rows(const f32x16 (&acc)[FM][FN], bf1
   }
 }
 
+// --------------------------------------------------------------------------------------
+// The shared contraction loop.  `Ops` supplies the operand-specific parts:
+//   ops.begin_group(step)        called once before the 8 loads of a stage are issued
+//   ops.load(I, step, lds_addr)  issues load instruction I (0..3 = A tile, 4..7 = B tile)
+//   ops.frag_a / frag_b          fragment reads from a landed stage
+//   Ops::EXTRA_LOADS             global loads issued by begin_group (counted by the waits)
+// Steps past the last one are clamped to it: their loads refill a stage nobody reads again,
+// which keeps the loop free of branches and the outstanding-load count constant.
+// --------------------------------------------------------------------------------------
+template <typename Ops>
+__device__ __forceinline__ void contraction_loop(Ops &ops, int nh, char *smem, int wm, int wn, int lane,
+                                                 f32x16 (&acc)[FR][FR]) {
+  constexpr int PER_GROUP = 2 * NLD + Ops::EXTRA_LOADS;
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
+  const int last = nh - 1;
+
+#pragma unroll
+  for (int i = 0; i < FR; ++i)
+#pragma unroll
+    for (int j = 0; j < FR; ++j)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+  if (nh <= 0) return;
+
+  // prologue: stages 0..2 requested at once
+#pragma unroll
+  for (int st = 0; st < NSTAGE - 1; ++st) {
+    int step = min(st, last);
+    ops.begin_group(step);
+#pragma unroll
+    for (int I = 0; I < 2 * NLD; ++I) ops.load(I, step, lds0 + st * STAGE_BYTES + (I / NLD) * TILE_BYTES);
+  }
+  wait_loads<PER_GROUP>();  // stages 0 and 1 have landed (loads complete in order)
+  __syncthreads();
+  bf16x8 fa[2][FR], fb[2][FR];
+#pragma unroll
+  for (int i = 0; i < FR; ++i) fa[0][i] = ops.frag_a(smem, wm * (TB / 2) + i * 32, 0, lane);
+#pragma unroll
+  for (int j = 0; j < FR; ++j) fb[0][j] = ops.frag_b(smem + TILE_BYTES, wn * (TB / 2) + j * 32, 0, lane);
+
+  for (int h = 0; h < nh; ++h) {
+    // stage h+1 has landed for every wavefront and nobody still reads stage h-1
+    wait_loads<PER_GROUP>();
+    __syncthreads();
+    const char *cur = smem + (h & 3) * STAGE_BYTES;
+    const char *nxt = smem + ((h + 1) & 3) * STAGE_BYTES;
+    const uint32_t fill = lds0 + ((h + 3) & 3) * STAGE_BYTES;
+    const int fill_step = min(h + 3, last);
+    ops.begin_group(fill_step);
+    sched_fence();
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      // fragments read during this sub-step: (stage h, kk = 1) or (stage h+1, kk = 0)
+      const char *src = kk == 0 ? cur : nxt;
+      const int nkk = 1 - kk;
+#pragma unroll
+      for (int g = 0; g < FR; ++g) {
+#pragma unroll
+        for (int j = 0; j < FR; ++j)
+          acc[g][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk][j], fa[kk][g], acc[g][j], 0, 0, 0);
+        // next fragments in the order the next sub-step consumes them: b0 a0 b1 | b2 b3 a1 | a2 a3
+        if (g == 0) {
+          fb[nkk][0] = ops.frag_b(src + TILE_BYTES, wn * (TB / 2) + 0 * 32, nkk, lane);
+          fa[nkk][0] = ops.frag_a(src, wm * (TB / 2) + 0 * 32, nkk, lane);
+          fb[nkk][1] = ops.frag_b(src + TILE_BYTES, wn * (TB / 2) + 1 * 32, nkk, lane);
+        } else if (g == 1) {
+          fb[nkk][2] = ops.frag_b(src + TILE_BYTES, wn * (TB / 2) + 2 * 32, nkk, lane);
+          fb[nkk][3] = ops.frag_b(src + TILE_BYTES, wn * (TB / 2) + 3 * 32, nkk, lane);
+          fa[nkk][1] = ops.frag_a(src, wm * (TB / 2) + 1 * 32, nkk, lane);
+        } else if (g == 2) {
+          fa[nkk][2] = ops.frag_a(src, wm * (TB / 2) + 2 * 32, nkk, lane);
+          fa[nkk][3] = ops.frag_a(src, wm * (TB / 2) + 3 * 32, nkk, lane);
+        }
+        // LDS reads ride behind the matrix instructions, then the group's global load
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
+        sched_fence();
+        const int I = kk * FR + g;
+        ops.load(I, fill_step, fill + (I / NLD) * TILE_BYTES);
+        sched_fence();
+      }
+    }
+  }
+  wait_loads<0>();  // drain the refills of the last three half-steps
+}
+
 // ======================================================================================
-// scatter2scatter: C[cmap(i), n0:n0+BN] = A[amap(i), :] * op(W[e])[:, n0:n0+BN]
+// scatter2scatter: C[cmap(i), n0:n0+256] = A[amap(i), :] * op(W[e])[:, n0:n0+256]
 // ======================================================================================
-template <bool TRANS_W, int BM, int BN>
+template <bool TRANS_W> struct S2SOps {
+  static constexpr int EXTRA_LOADS = 0;
+  const bf16_t *pa[NLD];   // per-lane source of each A load instruction at contraction offset 0
+  const bf16_t *pb[NLD];
+  size_t b_step;           // elements between consecutive half-steps of the B source
+  int uwave;
+  __device__ __forceinline__ void begin_group(int) {}
+  __device__ __forceinline__ void load(int I, int step, uint32_t tile_lds) {
+    if (I < NLD) load16_to_lds(pa[I] + (size_t)step * HK, tile_lds + inst_off(uwave, I));
+    else load16_to_lds(pb[I - NLD] + (size_t)step * b_step, tile_lds + inst_off(uwave, I - NLD));
+  }
+  __device__ __forceinline__ bf16x8 frag_a(const char *tile, int base, int kk, int lane) {
+    return kc_frag(tile, base, kk, lane);
+  }
+  __device__ __forceinline__ bf16x8 frag_b(const char *tile, int base, int kk, int lane) {
+    return TRANS_W ? kc_frag(tile, base, kk, lane) : tr_frag(tile, base, kk, lane);
+  }
+};
+
+template <bool TRANS_W>
 __global__ void __launch_bounds__(NTHREADS, 1) s2s_mfma_kernel(S2SArgs a, int tiles_n, int group_m) {
-  constexpr int FM = BM / 64, FN = BN / 64;              // 32x32 fragments per wave
-  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
 
   // ---- which tile
@@ -172,104 +270,103 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_mfma_kernel(S2SArgs a, int ti
   const int mt = grp * group_m + in_grp % group_m;
   const int nt = in_grp / group_m;
   int e, row0, row_end;
-  if (nt >= tiles_n || !locate_tile(a.offsets, a.E, BM, mt, e, row0, row_end)) return;
-  const int n0 = nt * BN;
+  if (nt >= tiles_n || !locate_tile(a.offsets, a.E, TB, mt, e, row0, row_end)) return;
+  const int n0 = nt * TB;
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;
   const bf16_t *A = (const bf16_t *)a.A;
   const bf16_t *W = (const bf16_t *)a.W + (size_t)e * a.w_stride;
 
-  // ---- per-lane source pointers (contraction offset 0); rows past the segment re-read its last row
-  const bf16_t *pa[BM / 32];
+  // ---- per-lane source pointers; rows past the segment re-read its last row (never stored)
+  S2SOps<TRANS_W> ops;
+  ops.uwave = __builtin_amdgcn_readfirstlane(wave);
 #pragma unroll
-  for (int I = 0; I < BM / 32; ++I) {
+  for (int I = 0; I < NLD; ++I) {
     int r, c;
-    kc_lane_slot<BM>(wave, lane, I, r, c);
+    kc_lane_slot(wave, lane, I, r, c);
     int i = min(row0 + r, row_end - 1);
-    pa[I] = A + (size_t)map_row(a.a_map, i) * a.K + c * 8;
+    ops.pa[I] = A + (size_t)map_row(a.a_map, i) * a.K + c * 8;
   }
-  const bf16_t *pb[BN / 32];
 #pragma unroll
-  for (int I = 0; I < BN / 32; ++I) {
+  for (int I = 0; I < NLD; ++I) {
     int r, c;
     if (TRANS_W) {  // KC tile over rows n of W (row stride ldw), contraction along the row
-      kc_lane_slot<BN>(wave, lane, I, r, c);
+      kc_lane_slot(wave, lane, I, r, c);
       int n = min(n0 + r, a.N - 1);
-      pb[I] = W + (size_t)n * a.ldw + c * 8;
-    } else {        // TR tile: contraction rows of W, BN columns
-      tr_lane_slot<BN>(wave, lane, I, r, c);
+      ops.pb[I] = W + (size_t)n * a.ldw + c * 8;
+    } else {        // TR tile: contraction rows of W, 256 columns
+      tr_lane_slot(wave, lane, I, r, c);
       int col = n0 + c * 8;
       if (col >= a.N) col = 0;
-      pb[I] = W + (size_t)r * a.ldw + col;
+      ops.pb[I] = W + (size_t)r * a.ldw + col;
     }
   }
-  const size_t b_step = TRANS_W ? (size_t)BK : (size_t)BK * a.ldw;
+  ops.b_step = TRANS_W ? (size_t)HK : (size_t)HK * a.ldw;
 
-  const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
-  const int uwave = __builtin_amdgcn_readfirstlane(wave);
-  auto issue = [&](int stage, int ks) {
-    const uint32_t at = lds0 + stage * STAGE, bt = at + A_BYTES;
-#pragma unroll
-    for (int I = 0; I < BM / 32; ++I) load16_to_lds(pa[I] + (size_t)ks * BK, at + kc_inst_off<BM>(uwave, I));
-#pragma unroll
-    for (int I = 0; I < BN / 32; ++I)
-      load16_to_lds(pb[I] + (size_t)ks * b_step, bt + (TRANS_W ? kc_inst_off<BN>(uwave, I) : tr_inst_off<BN>(uwave, I)));
-  };
-  auto frags = [&](const char *at, int kk, bf16x8(&fa)[FM], bf16x8(&fb)[FN]) {
-    const char *bt = at + A_BYTES;
-#pragma unroll
-    for (int i = 0; i < FM; ++i) fa[i] = kc_frag(at, wm * (BM / 2) + i * 32, kk, lane);
-#pragma unroll
-    for (int j = 0; j < FN; ++j)
-      fb[j] = TRANS_W ? kc_frag(bt, wn * (BN / 2) + j * 32, kk, lane) : tr_frag<BN>(bt, wn * (BN / 2) + j * 32, kk, lane);
-  };
-
-  f32x16 acc[FM][FN];
-#pragma unroll
-  for (int i = 0; i < FM; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
-
-  const int nsteps = a.K / BK;
-  issue(0, 0);
-  for (int ks = 0; ks < nsteps; ++ks) {
-    wait_all_loads();
-    __syncthreads();
-    const char *at = smem + (ks & 1) * STAGE;
-    bf16x8 fa[2][FM], fb[2][FN];
-    frags(at, 0, fa[0], fb[0]);
-    if (ks + 1 < nsteps) issue((ks + 1) & 1, ks + 1);
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      if (kk + 1 < BK / 16) frags(at, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
-      if (kk + 1 < BK / 16) interleave_mfma_dsread<FM * FN, FM + (TRANS_W ? FN : 2 * FN)>();
-    }
-  }
-  store_tile_rows<BM, BN, FM, FN>(acc, (bf16_t *)a.C, a.N, a.c_map, row0, row_end, n0, a.N, wm, wn, lane);
+  f32x16 acc[FR][FR];
+  contraction_loop(ops, a.K / HK, smem, wm, wn, lane, acc);
+  store_tile_rows(acc, (bf16_t *)a.C, a.N, a.c_map, row0, row_end, n0, a.N, wm, wn, lane);
 }
 
 // ======================================================================================
-// groupXTY: dW[e][m0:m0+BM, n0:n0+BN] = sum over the expert's rows i of A[amap(i), m]^T B[bmap(i), n]
+// groupXTY: dW[e][m0:m0+256, n0:n0+256] = sum over the expert's rows i of A[amap(i), m]^T B[bmap(i), n]
 // ======================================================================================
-template <int BM, int BN>
-__global__ void __launch_bounds__(NTHREADS, 1) dw_mfma_kernel(DWArgs a, int tiles_m, int tiles_n) {
-  constexpr int FM = BM / 64, FN = BN / 64;
-  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
+// Source-row numbers of a gathered operand come from the order indices.  Each wavefront keeps
+// a private ring of them in LDS, filled five half-steps ahead by a 4-byte direct-to-LDS load
+// (lanes 0..31: operand A rows of the step, lanes 32..63: operand B rows), so the gathered
+// tile loads never wait on an index lookup and all loads stay on one in-order counter.
+template <bool GATHER> struct DWOps {
+  static constexpr int EXTRA_LOADS = GATHER ? 1 : 0;
+  const bf16_t *A, *B;
+  const int32_t *oa, *ob;      // order indices per operand or nullptr (rows already grouped)
+  uint32_t magic_a, magic_b;   // ceil(2^32 / fan), 0 when fan == 1
+  int M, N, lo, hi, max_i;
+  int ra[NLD], ca[NLD], rb[NLD], cb[NLD];  // per load instruction: row within the step, column offset
+  int uwave, lane;
+  uint32_t ring_lds;           // LDS byte address of this wavefront's ring [8 slots][64]
+  const int *ring;
+  const bf16_t *pa[NLD], *pb[NLD];
+
+  __device__ __forceinline__ void fetch_indices(int step) {   // one 4-byte load per lane
+    int i = min(lo + step * HK + (lane & 31), max_i);
+    const int32_t *src = (lane < 32) ? (oa ? oa : ob) : (ob ? ob : oa);
+    load4_to_lds(src + i, ring_lds + (step & 7) * 256);
+  }
+  __device__ __forceinline__ int source_row(const int32_t *o, uint32_t magic, int step, int r, int half) {
+    int i = lo + step * HK + r;
+    if (i >= hi) return -1;
+    if (!GATHER || !o) return i;
+    uint32_t raw = (uint32_t)ring[(step & 7) * 64 + half * 32 + r];
+    return (int)(magic ? __umulhi(raw, magic) : raw);
+  }
+  __device__ __forceinline__ void begin_group(int step) {
+    if (GATHER) fetch_indices(step + 2);   // consumed two groups later
+#pragma unroll
+    for (int I = 0; I < NLD; ++I) {
+      int row = source_row(oa, magic_a, step, ra[I], 0);
+      pa[I] = (row >= 0) ? A + (size_t)row * M + ca[I] : (const bf16_t *)g_zero16;
+    }
+#pragma unroll
+    for (int I = 0; I < NLD; ++I) {
+      int row = source_row(ob, magic_b, step, rb[I], 1);
+      pb[I] = (row >= 0) ? B + (size_t)row * N + cb[I] : (const bf16_t *)g_zero16;
+    }
+  }
+  __device__ __forceinline__ void load(int I, int, uint32_t tile_lds) {
+    if (I < NLD) load16_to_lds(pa[I], tile_lds + inst_off(uwave, I));
+    else load16_to_lds(pb[I - NLD], tile_lds + inst_off(uwave, I - NLD));
+  }
+  __device__ __forceinline__ bf16x8 frag_a(const char *tile, int base, int kk, int l) { return tr_frag(tile, base, kk, l); }
+  __device__ __forceinline__ bf16x8 frag_b(const char *tile, int base, int kk, int l) { return tr_frag(tile, base, kk, l); }
+};
+
+template <bool GATHER>
+__global__ void __launch_bounds__(NTHREADS, 1) dw_mfma_kernel(DWArgs a, int tiles_m, int tiles_n, uint32_t magic_a,
+                                                              uint32_t magic_b) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   __shared__ int s_expert;
-  // Ring of source-row numbers, [slot][operand][row of the step]; -1 marks rows past the segment.
-  // The numbers of step s are fetched from the routing arrays two steps early by 128 threads,
-  // parked in a register, and published here one step early, so the gathered global->LDS
-  // loads never wait on an index lookup.
-  __shared__ int s_idx[4][2][BK];
+  __shared__ int s_ring[4][8][64];
 
   // Block ids map to tiles directly: consecutive blocks (dealt round-robin to the XCDs) share
   // an expert, so every XCD gets the same mix of long and short contractions.
@@ -289,115 +386,52 @@ __global__ void __launch_bounds__(NTHREADS, 1) dw_mfma_kernel(DWArgs a, int tile
   __syncthreads();
   const int e = s_expert;
   const int t = vid % per_expert;
-  const int m0 = (t % tiles_m) * BM, n0 = (t / tiles_m) * BN;
-  const int lo = a.offsets[e], hi = a.offsets[e + 1];
-  const int nsteps = (hi - lo + BK - 1) / BK;
-
+  const int m0 = (t % tiles_m) * TB, n0 = (t / tiles_m) * TB;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;
-  const bf16_t *A = (const bf16_t *)a.A;
-  const bf16_t *B = (const bf16_t *)a.B;
 
-  // per-lane tile slots: contraction row within the step and column offset (elements)
-  int ra[BM / 32], ca[BM / 32], rb[BN / 32], cb[BN / 32];
+  DWOps<GATHER> ops;
+  ops.A = (const bf16_t *)a.A;
+  ops.B = (const bf16_t *)a.B;
+  ops.oa = a.a_map.o;
+  ops.ob = a.b_map.o;
+  ops.magic_a = magic_a;
+  ops.magic_b = magic_b;
+  ops.M = a.M;
+  ops.N = a.N;
+  ops.lo = a.offsets[e];
+  ops.hi = a.offsets[e + 1];
+  ops.max_i = a.Tk - 1;
+  ops.uwave = __builtin_amdgcn_readfirstlane(wave);
+  ops.lane = lane;
+  ops.ring = &s_ring[wave][0][0];
+  ops.ring_lds = __builtin_amdgcn_readfirstlane(lds_address((const char *)&s_ring[wave][0][0]));
 #pragma unroll
-  for (int I = 0; I < BM / 32; ++I) {
+  for (int I = 0; I < NLD; ++I) {
     int c;
-    tr_lane_slot<BM>(wave, lane, I, ra[I], c);
-    ca[I] = m0 + c * 8;
-    if (ca[I] >= a.M) ca[I] = 0;
+    tr_lane_slot(wave, lane, I, ops.ra[I], c);
+    ops.ca[I] = m0 + c * 8;
+    if (ops.ca[I] >= a.M) ops.ca[I] = 0;
+    tr_lane_slot(wave, lane, I, ops.rb[I], c);
+    ops.cb[I] = n0 + c * 8;
+    if (ops.cb[I] >= a.N) ops.cb[I] = 0;
   }
-#pragma unroll
-  for (int I = 0; I < BN / 32; ++I) {
-    int c;
-    tr_lane_slot<BN>(wave, lane, I, rb[I], c);
-    cb[I] = n0 + c * 8;
-    if (cb[I] >= a.N) cb[I] = 0;
+  const int nh = (ops.hi - ops.lo + HK - 1) / HK;
+  if (GATHER && nh > 0) {   // the first three groups' row numbers must be in the ring before the loop resolves them
+    ops.fetch_indices(0);
+    ops.fetch_indices(1);
+    ops.fetch_indices(2);
+    wait_loads<0>();
   }
-  const int irow = threadIdx.x & 63, iop = threadIdx.x >> 6;  // waves 0/1 look up rows of A/B
-  auto lookup = [&](int ks) -> int {
-    int i = lo + ks * BK + irow;
-    if (iop >= 2 || i >= hi) return -1;
-    return iop == 0 ? map_row(a.a_map, i) : map_row(a.b_map, i);
-  };
-  // source pointers of one step; rows past the segment read a block of zeros so they add
-  // nothing to the sum
-  const bf16_t *pa[BM / 32], *pb[BN / 32];
-  auto resolve = [&](int ks) {
-    const int slot = ks & 3;
-#pragma unroll
-    for (int I = 0; I < BM / 32; ++I) {
-      int row = s_idx[slot][0][ra[I]];
-      pa[I] = (row >= 0) ? A + (size_t)row * a.M + ca[I] : (const bf16_t *)g_zero16;
-    }
-#pragma unroll
-    for (int I = 0; I < BN / 32; ++I) {
-      int row = s_idx[slot][1][rb[I]];
-      pb[I] = (row >= 0) ? B + (size_t)row * a.N + cb[I] : (const bf16_t *)g_zero16;
-    }
-  };
-  const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
-  const int uwave = __builtin_amdgcn_readfirstlane(wave);
-  auto issue = [&](int stage) {
-    const uint32_t at = lds0 + stage * STAGE, bt = at + A_BYTES;
-#pragma unroll
-    for (int I = 0; I < BM / 32; ++I) load16_to_lds(pa[I], at + tr_inst_off<BM>(uwave, I));
-#pragma unroll
-    for (int I = 0; I < BN / 32; ++I) load16_to_lds(pb[I], bt + tr_inst_off<BN>(uwave, I));
-  };
-  auto frags = [&](const char *at, int kk, bf16x8(&fa)[FM], bf16x8(&fb)[FN]) {
-    const char *bt = at + A_BYTES;
-#pragma unroll
-    for (int i = 0; i < FM; ++i) fa[i] = tr_frag<BM>(at, wm * (BM / 2) + i * 32, kk, lane);
-#pragma unroll
-    for (int j = 0; j < FN; ++j) fb[j] = tr_frag<BN>(bt, wn * (BN / 2) + j * 32, kk, lane);
-  };
 
-  f32x16 acc[FM][FN];
-#pragma unroll
-  for (int i = 0; i < FM; ++i)
-#pragma unroll
-    for (int j = 0; j < FN; ++j)
-#pragma unroll
-      for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
-
-  if (threadIdx.x < 128) {
-    s_idx[0][iop][irow] = lookup(0);
-    s_idx[1][iop][irow] = lookup(1);
-  }
-  int parked = lookup(2);
-  __syncthreads();
-  if (nsteps > 0) {
-    resolve(0);
-    issue(0);
-  }
-  for (int ks = 0; ks < nsteps; ++ks) {
-    wait_all_loads();
-    if (threadIdx.x < 128) s_idx[(ks + 2) & 3][iop][irow] = parked;
-    __syncthreads();
-    const char *at = smem + (ks & 1) * STAGE;
-    bf16x8 fa[2][FM], fb[2][FN];
-    frags(at, 0, fa[0], fb[0]);
-    if (ks + 1 < nsteps) {
-      resolve(ks + 1);
-      issue((ks + 1) & 1);
-    }
-    parked = lookup(ks + 3);
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      if (kk + 1 < BK / 16) frags(at, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
-#pragma unroll
-      for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
-      if (kk + 1 < BK / 16) interleave_mfma_dsread<FM * FN, 2 * FM + 2 * FN>();
-    }
-  }
+  f32x16 acc[FR][FR];
+  contraction_loop(ops, nh, smem, wm, wn, lane, acc);
   bf16_t *dW = (bf16_t *)a.dW + (size_t)e * a.M * a.N;
   RowMap ident{nullptr, 1};
-  store_tile_rows<BM, BN, FM, FN>(acc, dW, a.N, ident, m0, a.M, n0, a.N, wm, wn, lane);
+  store_tile_rows(acc, dW, a.N, ident, m0, a.M, n0, a.N, wm, wn, lane);
 }
+
+constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
 
 template <typename K> int set_lds_limit(K kernel, int bytes) {
   return hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess
@@ -405,51 +439,55 @@ template <typename K> int set_lds_limit(K kernel, int bytes) {
              : SMOE_ERR_HIP;
 }
 
-template <bool TRANS_W, int BM, int BN>
-int launch_s2s_cfg(hipStream_t s, const S2SArgs &a) {
-  constexpr int LDS = 2 * (BM + BN) * BK * 2;
-  static int attr_rc = set_lds_limit(s2s_mfma_kernel<TRANS_W, BM, BN>, LDS);
+template <bool TRANS_W> int launch_s2s_cfg(hipStream_t s, const S2SArgs &a) {
+  static int attr_rc = set_lds_limit(s2s_mfma_kernel<TRANS_W>, LDS_BYTES);
   if (attr_rc != SMOE_OK) return attr_rc;
-  int tiles_n = ceil_div(a.N, BN);
-  int tiles_m = ceil_div(a.Tk, BM) + a.E;     // upper bound on sum_e ceil(n_e / BM)
+  int tiles_n = ceil_div(a.N, TB);
+  int tiles_m = ceil_div(a.Tk, TB) + a.E;     // upper bound on sum_e ceil(n_e / 256)
   int group_m = 4;
   long long total = (long long)ceil_div(tiles_m, group_m) * group_m * tiles_n;
   total = (total + 7) / 8 * 8;
   if (total > 0x7fffffffLL) return SMOE_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL((s2s_mfma_kernel<TRANS_W, BM, BN>), dim3((unsigned)total), dim3(NTHREADS), LDS, s, a, tiles_n,
+  hipLaunchKernelGGL((s2s_mfma_kernel<TRANS_W>), dim3((unsigned)total), dim3(NTHREADS), LDS_BYTES, s, a, tiles_n,
                      group_m);
   SMOE_LAUNCH_CHECK();
   return SMOE_OK;
 }
 
-template <int BM, int BN>
-int launch_dw_cfg(hipStream_t s, const DWArgs &a) {
-  constexpr int LDS = 2 * (BM + BN) * BK * 2;
-  static int attr_rc = set_lds_limit(dw_mfma_kernel<BM, BN>, LDS);
+// ceil(2^32 / fan): umulhi(x, magic) == x / fan whenever x * fan < 2^32
+uint32_t division_magic(int fan) { return fan > 1 ? (uint32_t)((0x100000000ULL + fan - 1) / fan) : 0u; }
+
+template <bool GATHER> int launch_dw_cfg(hipStream_t s, const DWArgs &a) {
+  static int attr_rc = set_lds_limit(dw_mfma_kernel<GATHER>, LDS_BYTES);
   if (attr_rc != SMOE_OK) return attr_rc;
-  int tiles_m = ceil_div(a.M, BM), tiles_n = ceil_div(a.N, BN);
+  int tiles_m = ceil_div(a.M, TB), tiles_n = ceil_div(a.N, TB);
   long long total = (long long)a.E * tiles_m * tiles_n;
-  total = (total + 7) / 8 * 8;
   if (total > 0x7fffffffLL) return SMOE_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL((dw_mfma_kernel<BM, BN>), dim3((unsigned)total), dim3(NTHREADS), LDS, s, a, tiles_m, tiles_n);
+  hipLaunchKernelGGL((dw_mfma_kernel<GATHER>), dim3((unsigned)total), dim3(NTHREADS), LDS_BYTES, s, a, tiles_m,
+                     tiles_n, division_magic(a.a_map.o ? a.a_map.fan : 1), division_magic(a.b_map.o ? a.b_map.fan : 1));
   SMOE_LAUNCH_CHECK();
   return SMOE_OK;
 }
 
 }  // namespace
 
-// The matrix-core kernels take contraction lengths that are multiples of 64 (no zero fill
+// The matrix-core kernels take contraction lengths that are multiples of 32 (no zero fill
 // along k) and widths that are multiples of 8 (16-byte chunks never straddle a row end).
-bool s2s_mfma_supported(const S2SArgs &a) { return a.K % BK == 0 && a.N % 8 == 0 && a.ldw % 8 == 0 && a.Tk > 0; }
-bool dw_mfma_supported(const DWArgs &a) { return a.M % 8 == 0 && a.N % 8 == 0; }
+bool s2s_mfma_supported(const S2SArgs &a) { return a.K % HK == 0 && a.N % 8 == 0 && a.ldw % 8 == 0 && a.Tk > 0; }
+// groupXTY divides order indices by the fan-out with a multiply-high, exact while Tk * fan < 2^32.
+bool dw_mfma_supported(const DWArgs &a) {
+  long long fan = 1;
+  if (a.a_map.o && a.a_map.fan > fan) fan = a.a_map.fan;
+  if (a.b_map.o && a.b_map.fan > fan) fan = a.b_map.fan;
+  return a.M % 8 == 0 && a.N % 8 == 0 && a.Tk > 0 && (long long)a.Tk * fan < 0x100000000LL;
+}
 
 int launch_s2s_mfma(hipStream_t s, const S2SArgs &a, int num_cu) {
   (void)num_cu;
-  if (a.trans_w) return launch_s2s_cfg<true, 256, 256>(s, a);
-  return launch_s2s_cfg<false, 256, 256>(s, a);
+  return a.trans_w ? launch_s2s_cfg<true>(s, a) : launch_s2s_cfg<false>(s, a);
 }
 
 int launch_dw_mfma(hipStream_t s, const DWArgs &a, int num_cu) {
   (void)num_cu;
-  return launch_dw_cfg<256, 256>(s, a);
+  return (a.a_map.o || a.b_map.o) ? launch_dw_cfg<true>(s, a) : launch_dw_cfg<false>(s, a);
 }
