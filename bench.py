@@ -70,6 +70,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the oracle baseline (0 = skip)")
     ap.add_argument("--kernel-reps", type=int, default=20)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB elementwise copy kernel (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (data-parallel sharding is a design note); use --gpus 1",
@@ -144,6 +146,20 @@ def main():
     s2s_flops = 2.0 * cfg.Tk * cfg.d_model * d_h
     achieved = s2s_flops / (ms_s2s * 1e-3) / 1e12
 
+    if args.calibrate_copy:   # known traffic: reads 1 GiB, writes 1 GiB per launch
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"s2s_fwd1_{cfg.name}_hbm_traffic.json")
+    if os.path.exists(tpath):   # HBM bytes per launch measured with rocprofv3 --pmc (see the file for the commands)
+        with open(tpath) as f:
+            traffic = json.load(f).get("hbm_bytes_per_launch")
+
     out = {
         "metric": "SMoE MLP fwd+bwd GEMM throughput per layer (routing + Alg. 3 forward + backward)",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -159,7 +175,7 @@ def main():
         "phases_ms": {"routing": ms_route, "mlp_fwd": ms_fwd, "mlp_bwd": ms_bwd},
         "roofline": {"bound": "mfma", "kernel": "s2s_mfma_kernel (ParallelLinear #1, scattered->grouped)",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-                     "ms_per_launch": ms_s2s, "flop_per_launch": s2s_flops, "traffic": None},
+                     "ms_per_launch": ms_s2s, "flop_per_launch": s2s_flops, "traffic": traffic},
     }
     if args.cpu_seconds > 0:
         out["cpu_baseline"] = cpu_baseline(case, cfg, gates.cpu().numpy().astype(np.float64), ei.cpu().numpy(),
