@@ -100,20 +100,34 @@ __device__ __forceinline__ bf16x8 tr_frag(const char *tile, int cbase, int kk, i
 // byte offset inside an operand tile of a wavefront's load instruction (both layouts: 1 KB each)
 __device__ __forceinline__ int inst_off(int wave, int inst) { return (wave * NLD + inst) * 1024; }
 
-// Finds expert and first row of M-tile `tile` when each expert's segment is cut into bm-row tiles.
-__device__ __forceinline__ bool locate_tile(const int32_t *offsets, int E, int bm, int tile, int &e, int &row0,
+// Finds expert and first row of M-tile `tile` when each expert's segment is cut into 256-row
+// tiles.  Every wavefront runs the search on its own: lane x looks at expert c0 + x, a wave
+// prefix sum counts the tiles before it, a ballot picks the expert that owns `tile`.
+__device__ __forceinline__ bool locate_tile(const int32_t *offsets, int E, int tile, int lane, int &e, int &row0,
                                             int &row_end) {
-  int acc = 0;
-  for (int x = 0; x < E; ++x) {
-    int lo = offsets[x], hi = offsets[x + 1];
-    int nt = (hi - lo + bm - 1) / bm;
-    if (tile < acc + nt) {
-      e = x;
-      row0 = lo + (tile - acc) * bm;
-      row_end = hi;
+  int base = 0;
+  for (int c0 = 0; c0 < E; c0 += 64) {
+    int x = c0 + lane;
+    int lo = 0, hi = 0;
+    if (x < E) { lo = offsets[x]; hi = offsets[x + 1]; }
+    int nt = (hi - lo + TB - 1) / TB;
+    int incl = nt;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      int up = __shfl_up(incl, d, 64);
+      if (lane >= d) incl += up;
+    }
+    int total = __shfl(incl, 63, 64);
+    if (tile < base + total) {
+      unsigned long long owns = __ballot(base + incl > tile);
+      int first = __ffsll((long long)owns) - 1;
+      int before = __shfl(incl - nt, first, 64);
+      e = c0 + first;
+      row0 = __shfl(lo, first, 64) + (tile - base - before) * TB;
+      row_end = __shfl(hi, first, 64);
       return true;
     }
-    acc += nt;
+    base += total;
   }
   return false;
 }
@@ -125,25 +139,40 @@ __device__ __forceinline__ int xcd_contiguous_id(int pid, int grid) {
   return (pid & 7) * per + (pid >> 3);
 }
 
-__device__ __forceinline__ void store_tile_rows(const f32x16 (&acc)[FR][FR], bf16_t *C, int ldc, const RowMap &cmap,
-                                                int row0, int row_end, int col0, int ncols, int wm, int wn, int lane) {
+// Epilogue: the accumulators of a wavefront (128 x 128, a lane holds 4 consecutive columns of
+// one row per register quad) are rounded to bf16, turned into row-major order through a
+// private LDS patch (32 rows x 272 B, the 16 B pad keeps the 8-byte writes conflict free) and
+// leave as 16-byte stores that cover 256 contiguous bytes of 4 destination rows each -- whole
+// cache lines, also when the rows are scattered.  s_rows[r] is the destination row of tile row
+// r, or -1 for rows past the segment / matrix end.
+constexpr int EPI_ROW_BYTES = 272;
+constexpr int EPI_WAVE_BYTES = 32 * EPI_ROW_BYTES;
+__device__ __forceinline__ void store_tile(const f32x16 (&acc)[FR][FR], char *smem, const int *s_rows, bf16_t *C,
+                                           int ldc, int col0, int ncols, int wave, int wm, int wn, int lane) {
+  __syncthreads();  // every wavefront is done with the stage ring
+  char *patch = smem + wave * EPI_WAVE_BYTES;
+  const int wcol = col0 + wn * (TB / 2);
 #pragma unroll
   for (int fm = 0; fm < FR; ++fm) {
-    int i = row0 + wm * (TB / 2) + fm * 32 + (lane & 31);
-    if (i >= row_end) continue;
-    bf16_t *crow = C + (size_t)map_row(cmap, i) * ldc;
 #pragma unroll
     for (int fn = 0; fn < FR; ++fn) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        int n = col0 + wn * (TB / 2) + fn * 32 + 8 * g + 4 * (lane >> 5);
-        if (n < ncols) {
-          bf16x4 v;
+        bf16x4 v;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) v[q] = (bf16_t)acc[fm][fn][g * 4 + q];
-          *reinterpret_cast<bf16x4 *>(crow + n) = v;
-        }
+        for (int q = 0; q < 4; ++q) v[q] = (bf16_t)acc[fm][fn][g * 4 + q];
+        int col = fn * 32 + 8 * g + 4 * (lane >> 5);
+        *reinterpret_cast<bf16x4 *>(patch + (lane & 31) * EPI_ROW_BYTES + col * 2) = v;
       }
+    }
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      int r = it * 4 + (lane >> 4);
+      int chunk = lane & 15;
+      bf16x8 v = *reinterpret_cast<const bf16x8 *>(patch + r * EPI_ROW_BYTES + chunk * 16);
+      int dst = s_rows[wm * (TB / 2) + fm * 32 + r];
+      int col = wcol + chunk * 8;
+      if (dst >= 0 && col < ncols) *reinterpret_cast<bf16x8 *>(C + (size_t)dst * ldc + col) = v;
     }
   }
 }
@@ -262,6 +291,7 @@ template <bool TRANS_W> struct S2SOps {
 template <bool TRANS_W>
 __global__ void __launch_bounds__(NTHREADS, 1) s2s_mfma_kernel(S2SArgs a, int tiles_n, int group_m) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
+  __shared__ int s_rows[TB];
 
   // ---- which tile
   const int vid = xcd_contiguous_id(blockIdx.x, gridDim.x);
@@ -270,13 +300,17 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_mfma_kernel(S2SArgs a, int ti
   const int mt = grp * group_m + in_grp % group_m;
   const int nt = in_grp / group_m;
   int e, row0, row_end;
-  if (nt >= tiles_n || !locate_tile(a.offsets, a.E, TB, mt, e, row0, row_end)) return;
+  if (nt >= tiles_n || !locate_tile(a.offsets, a.E, mt, threadIdx.x & 63, e, row0, row_end)) return;
   const int n0 = nt * TB;
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;
   const bf16_t *A = (const bf16_t *)a.A;
   const bf16_t *W = (const bf16_t *)a.W + (size_t)e * a.w_stride;
+  {  // destination row of every tile row (read again by the epilogue, after the loop's barriers)
+    int i = row0 + (int)threadIdx.x;
+    s_rows[threadIdx.x] = (i < row_end) ? map_row(a.c_map, i) : -1;
+  }
 
   // ---- per-lane source pointers; rows past the segment re-read its last row (never stored)
   S2SOps<TRANS_W> ops;
@@ -306,7 +340,7 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_mfma_kernel(S2SArgs a, int ti
 
   f32x16 acc[FR][FR];
   contraction_loop(ops, a.K / HK, smem, wm, wn, lane, acc);
-  store_tile_rows(acc, (bf16_t *)a.C, a.N, a.c_map, row0, row_end, n0, a.N, wm, wn, lane);
+  store_tile(acc, smem, s_rows, (bf16_t *)a.C, a.N, n0, a.N, wave, wm, wn, lane);
 }
 
 // ======================================================================================
@@ -366,6 +400,7 @@ __global__ void __launch_bounds__(NTHREADS, 1) dw_mfma_kernel(DWArgs a, int tile
                                                               uint32_t magic_b) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   __shared__ int s_expert;
+  __shared__ int s_rows[TB];
   __shared__ int s_ring[4][8][64];
 
   // Block ids map to tiles directly: consecutive blocks (dealt round-robin to the XCDs) share
@@ -389,6 +424,7 @@ __global__ void __launch_bounds__(NTHREADS, 1) dw_mfma_kernel(DWArgs a, int tile
   const int m0 = (t % tiles_m) * TB, n0 = (t / tiles_m) * TB;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;
+  s_rows[threadIdx.x] = (m0 + (int)threadIdx.x < a.M) ? m0 + (int)threadIdx.x : -1;
 
   DWOps<GATHER> ops;
   ops.A = (const bf16_t *)a.A;
@@ -427,8 +463,7 @@ __global__ void __launch_bounds__(NTHREADS, 1) dw_mfma_kernel(DWArgs a, int tile
   f32x16 acc[FR][FR];
   contraction_loop(ops, nh, smem, wm, wn, lane, acc);
   bf16_t *dW = (bf16_t *)a.dW + (size_t)e * a.M * a.N;
-  RowMap ident{nullptr, 1};
-  store_tile_rows(acc, dW, a.N, ident, m0, a.M, n0, a.N, wm, wn, lane);
+  store_tile(acc, smem, s_rows, dW, a.N, n0, a.N, wave, wm, wn, lane);
 }
 
 constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
