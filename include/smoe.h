@@ -75,8 +75,9 @@ const char *smoe_strerror(int status);
 /* ABI version, bumped when a signature changes. */
 int smoe_abi_version(void);
 
-/* Selects the GEMM kernel family: 0 = automatic (matrix-core kernels whenever the shape
- * allows), 1 = force the plain tiled kernels (testing aid).  Host-only, not thread safe. */
+/* Selects the GEMM kernel family: 0 = automatic (persistent matrix-core kernels whenever the
+ * shape allows), 1 = force the plain tiled kernels, 2 = matrix-core kernels with one block per
+ * tile (1 and 2 are testing aids).  Host-only, not thread safe. */
 int smoe_set_kernel_mode(smoe_ctx *ctx, int mode);
 
 /* ---- routing: Sec. 3.1 step 1 -------------------------------------------------------

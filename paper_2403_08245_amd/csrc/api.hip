@@ -16,11 +16,12 @@ bool width_ok(smoe_dtype dt, int d) { return d > 0 && d % (int)(16 / dtype_size(
 bool dtype_ok(int dt) { return dt == SMOE_F32 || dt == SMOE_BF16; }
 
 int run_s2s(smoe_ctx *ctx, hipStream_t s, smoe_dtype dt, const S2SArgs &a) {
-  if (dt == SMOE_BF16 && ctx->kernel_mode == 0 && s2s_mfma_supported(a)) return launch_s2s_mfma(s, a, ctx->num_cu);
+  if (dt == SMOE_BF16 && ctx->kernel_mode == 0 && s2s_stream_supported(a)) return launch_s2s_stream(s, a);
+  if (dt == SMOE_BF16 && ctx->kernel_mode != 1 && s2s_mfma_supported(a)) return launch_s2s_mfma(s, a, ctx->num_cu);
   return launch_s2s_plain(s, dt, a);
 }
 int run_dw(smoe_ctx *ctx, hipStream_t s, smoe_dtype dt, const DWArgs &a) {
-  if (dt == SMOE_BF16 && ctx->kernel_mode == 0 && dw_mfma_supported(a)) return launch_dw_mfma(s, a, ctx->num_cu);
+  if (dt == SMOE_BF16 && ctx->kernel_mode != 1 && dw_mfma_supported(a)) return launch_dw_mfma(s, a, ctx->num_cu);
   return launch_dw_plain(s, dt, a);
 }
 
@@ -76,7 +77,7 @@ int smoe_create(smoe_ctx **out, int device) {
 void smoe_destroy(smoe_ctx *ctx) { delete ctx; }
 
 int smoe_set_kernel_mode(smoe_ctx *ctx, int mode) {
-  if (!ctx || mode < 0 || mode > 1) return SMOE_ERR_INVALID_ARG;
+  if (!ctx || mode < 0 || mode > 2) return SMOE_ERR_INVALID_ARG;
   ctx->kernel_mode = mode;
   return SMOE_OK;
 }

@@ -84,3 +84,6 @@ bool s2s_mfma_supported(const S2SArgs &a);
 bool dw_mfma_supported(const DWArgs &a);
 int launch_s2s_mfma(hipStream_t s, const S2SArgs &a, int num_cu);
 int launch_dw_mfma(hipStream_t s, const DWArgs &a, int num_cu);
+// persistent tile-stream kernels (gemm_stream.hip)
+bool s2s_stream_supported(const S2SArgs &a);
+int launch_s2s_stream(hipStream_t s, const S2SArgs &a);

@@ -1,0 +1,349 @@
+// Persistent ("stream") form of the bf16 matrix-core grouped GEMMs.
+//
+// One block per compute unit walks a list of 256x256 output tiles.  The four-stage LDS ring of
+// the contraction loop never drains between tiles: the loader side runs three half-steps ahead
+// of the multiplying side and simply moves on to the next tile's operand rows, so the next
+// tile's first stages land while the current tile is being finished and written out.  Per tile
+// this removes the block launch, the pipeline fill and the tile search from the critical path;
+// what remains is the epilogue (accumulators -> bf16 -> LDS patch -> whole-line stores).
+//
+// Both sides visit the same sequence of slots (one per half-step, at least one per tile) with a
+// fixed lag.  Exactly eight tile loads (plus the index load of a gathered groupXTY) are issued
+// per slot -- slots past the end of the list repeat a valid address -- so one constant
+// `s_waitcnt vmcnt` per slot orders everything.  Row indices travel through LDS by
+// direct-to-LDS loads as well: no ordinary global load sits in the loop, so the compiler never
+// inserts a full wait in front of the loads that are meant to stay in flight.
+#include "mfma_common.h"
+#include <type_traits>
+
+namespace {
+
+constexpr int RING_BYTES = NSTAGE * STAGE_BYTES;          // 128 KB
+constexpr int EPI_ROW_BYTES = 144;                        // 64 bf16 columns + 16 B pad
+constexpr int EPI_WAVE_BYTES = 32 * EPI_ROW_BYTES;
+constexpr int STREAM_LDS_BYTES = RING_BYTES + 4 * EPI_WAVE_BYTES;
+constexpr int MAX_E = 256;                                // expert offsets are cached in LDS
+constexpr int STREAM_GRID = 256;                          // persistent blocks (one per CU)
+
+// Epilogue of one wavefront: its 128x128 accumulators leave in 8 passes of 32 rows x 64
+// columns through a private LDS patch; every store instruction writes full 128-byte lines of
+// 8 destination rows.  dst_row(r) gives the destination row of wave-tile row r or -1.
+// Moves one accumulator element out of the accumulation register file right where it is
+// used.  Left to itself the register allocator copies all 256 accumulators of a lane into
+// ordinary registers at the top of the epilogue, which cannot fit beside the operand
+// fragments and load addresses that stay live for the next tile.
+__device__ __forceinline__ float acc_read(float a) {
+  float v;
+  __asm__ volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+  return v;
+}
+
+template <typename RowFn>
+__device__ __forceinline__ void store_wave_tile(const f32x16 (&acc)[FR][FR], char *patch, RowFn dst_row, bf16_t *C,
+                                                int ldc, int wcol, int ncols, int lane) {
+  // the last matrix instructions must have retired before their results are read by hand
+  __asm__ volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+  for (int fm = 0; fm < FR; ++fm) {
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      sched_fence();   // one pass at a time: keeps the accumulator reads from piling up in registers
+#pragma unroll
+      for (int f2 = 0; f2 < 2; ++f2) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 v;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) v[q] = (bf16_t)acc_read(acc[fm][half * 2 + f2][g * 4 + q]);
+          int col = f2 * 32 + 8 * g + 4 * (lane >> 5);
+          *reinterpret_cast<bf16x4 *>(patch + (lane & 31) * EPI_ROW_BYTES + col * 2) = v;
+        }
+      }
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        int r = it * 8 + (lane >> 3);
+        int chunk = lane & 7;
+        bf16x8 v = *reinterpret_cast<const bf16x8 *>(patch + r * EPI_ROW_BYTES + chunk * 16);
+        int dst = dst_row(fm * 32 + r);
+        int col = wcol + half * 64 + chunk * 8;
+        bf16_t *p = (dst >= 0 && col < ncols) ? C + (size_t)dst * ldc + col : (bf16_t *)g_trash + lane * 8;
+        *reinterpret_cast<bf16x8 *>(p) = v;   // straight-line code: masked lanes hit the landing zone
+      }
+    }
+  }
+}
+
+// One half-step of the contraction: 32 matrix instructions on the landed stage `cur`, the
+// fragment reads of its second half and of the next stage's first half riding behind them, and
+// the eight loads of the stage being refilled, one per four matrix instructions.  FIRST starts
+// a tile: its first sixteen products overwrite the accumulators instead of adding to them.
+template <bool FIRST, typename Ops>
+__device__ __forceinline__ void half_step(Ops &ops, const char *cur, const char *nxt, uint32_t fill, int wm, int wn,
+                                          int lane, bf16x8 (&fa)[2][FR], bf16x8 (&fb)[2][FR], f32x16 (&acc)[FR][FR]) {
+  f32x16 zero;
+#pragma unroll
+  for (int q = 0; q < 16; ++q) zero[q] = 0.f;
+  sched_fence();
+#pragma unroll
+  for (int kk = 0; kk < 2; ++kk) {
+    const char *src = kk == 0 ? cur : nxt;
+    const int nkk = 1 - kk;
+#pragma unroll
+    for (int g = 0; g < FR; ++g) {
+#pragma unroll
+      for (int j = 0; j < FR; ++j)
+        acc[g][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk][j], fa[kk][g], (FIRST && kk == 0) ? zero : acc[g][j],
+                                                            0, 0, 0);
+      // next fragments in the order the next sub-step consumes them: b0 a0 b1 | b2 b3 a1 | a2 a3
+      if (g == 0) {
+        fb[nkk][0] = ops.frag_b(src + TILE_BYTES, wn * (TB / 2) + 0 * 32, nkk, lane);
+        fa[nkk][0] = ops.frag_a(src, wm * (TB / 2) + 0 * 32, nkk, lane);
+        fb[nkk][1] = ops.frag_b(src + TILE_BYTES, wn * (TB / 2) + 1 * 32, nkk, lane);
+      } else if (g == 1) {
+        fb[nkk][2] = ops.frag_b(src + TILE_BYTES, wn * (TB / 2) + 2 * 32, nkk, lane);
+        fb[nkk][3] = ops.frag_b(src + TILE_BYTES, wn * (TB / 2) + 3 * 32, nkk, lane);
+        fa[nkk][1] = ops.frag_a(src, wm * (TB / 2) + 1 * 32, nkk, lane);
+      } else if (g == 2) {
+        fa[nkk][2] = ops.frag_a(src, wm * (TB / 2) + 2 * 32, nkk, lane);
+        fa[nkk][3] = ops.frag_a(src, wm * (TB / 2) + 3 * 32, nkk, lane);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      }
+      sched_fence();
+      const int I = kk * FR + g;
+      ops.load(I, fill + (I / NLD) * TILE_BYTES);
+      sched_fence();
+    }
+  }
+}
+
+// ======================================================================================
+// scatter2scatter, persistent
+// ======================================================================================
+struct S2STile {
+  int seq;                    // position in this block's tile list (-1 before the first)
+  int ord;                    // running number of the tile among the block's valid tiles
+  int e, row0, row_end, n0;
+};
+
+template <bool TRANS_W> struct S2SStreamOps {
+  const bf16_t *pa[NLD], *pb[NLD];   // per-lane sources of the loader's current tile at contraction offset 0
+  size_t b_step;
+  int step;                          // half-step the next loads fetch
+  int uwave;
+  __device__ __forceinline__ void load(int I, uint32_t tile_lds) {
+    if (I < NLD) load16_to_lds(pa[I] + (size_t)step * HK, tile_lds + inst_off(uwave, I));
+    else load16_to_lds(pb[I - NLD] + (size_t)step * b_step, tile_lds + inst_off(uwave, I - NLD));
+  }
+  __device__ __forceinline__ bf16x8 frag_a(const char *tile, int base, int kk, int lane) {
+    return kc_frag(tile, base, kk, lane);
+  }
+  __device__ __forceinline__ bf16x8 frag_b(const char *tile, int base, int kk, int lane) {
+    return TRANS_W ? kc_frag(tile, base, kk, lane) : tr_frag(tile, base, kk, lane);
+  }
+};
+
+template <bool TRANS_W, bool SCATTER_OUT>
+__global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int tiles_n, int group_m, int total_vids,
+                                                                 uint32_t magic_a) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  __shared__ int s_off[MAX_E + 1];
+  __shared__ int s_idx[3][TB];   // order indices of the rows of up to three open tiles
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int uwave = __builtin_amdgcn_readfirstlane(wave);
+  const int G = gridDim.x;
+  const int slot_in_round = ((int)blockIdx.x & 7) * (G >> 3) + ((int)blockIdx.x >> 3);  // XCD-contiguous tiles
+  const int nh = a.K / HK;
+  const int32_t *o = a.a_map.o ? a.a_map.o : a.c_map.o;   // both maps use the same order indices
+  const bf16_t *A = (const bf16_t *)a.A;
+
+  for (int i = threadIdx.x; i <= a.E; i += NTHREADS) s_off[i] = a.offsets[i];
+  __syncthreads();
+
+  // next valid tile of this block after t (tiles whose M index lies past the last segment are skipped)
+  auto next_tile = [&](S2STile &t) -> bool {
+    const int per_group = group_m * tiles_n;
+    for (int seq = t.seq + 1;; ++seq) {
+      int vid = seq * G + slot_in_round;
+      if (vid >= total_vids) return false;
+      int grp = vid / per_group, in_grp = vid % per_group;
+      int mt = grp * group_m + in_grp % group_m, nt = in_grp / group_m;
+      int e, row0, row_end;
+      if (locate_tile(s_off, a.E, mt, lane, e, row0, row_end)) {
+        t.seq = seq;
+        t.ord += 1;
+        t.e = __builtin_amdgcn_readfirstlane(e);
+        t.row0 = __builtin_amdgcn_readfirstlane(row0);
+        t.row_end = __builtin_amdgcn_readfirstlane(row_end);
+        t.n0 = nt * TB;
+        return true;
+      }
+    }
+  };
+  // order indices of a tile's 256 rows -> s_idx[ord % 3] (rows past the segment repeat its last row)
+  auto fetch_rows = [&](const S2STile &t) {
+    if (!o) return;
+    int i = min(t.row0 + wave * 64 + lane, t.row_end - 1);
+    load4_to_lds(o + i, __builtin_amdgcn_readfirstlane(lds_address((const char *)&s_idx[t.ord % 3][0])) + uwave * 256);
+  };
+
+  S2SStreamOps<TRANS_W> ops;
+  ops.uwave = uwave;
+  ops.b_step = TRANS_W ? (size_t)HK : (size_t)HK * a.ldw;
+  auto setup_pointers = [&](const S2STile &t) {
+    const bf16_t *W = (const bf16_t *)a.W + (size_t)t.e * a.w_stride;
+    const int *idx = &s_idx[t.ord % 3][0];
+#pragma unroll
+    for (int I = 0; I < NLD; ++I) {
+      int r, c;
+      kc_lane_slot(wave, lane, I, r, c);
+      int src;
+      if (a.a_map.o) {
+        uint32_t slot = (uint32_t)idx[r];
+        src = (int)(magic_a ? __umulhi(slot, magic_a) : slot);
+      } else {
+        src = min(t.row0 + r, t.row_end - 1);
+      }
+      ops.pa[I] = A + (size_t)src * a.K + c * 8;
+    }
+#pragma unroll
+    for (int I = 0; I < NLD; ++I) {
+      int r, c;
+      if (TRANS_W) {
+        kc_lane_slot(wave, lane, I, r, c);
+        int n = min(t.n0 + r, a.N - 1);
+        ops.pb[I] = W + (size_t)n * a.ldw + c * 8;
+      } else {
+        tr_lane_slot(wave, lane, I, r, c);
+        int col = t.n0 + c * 8;
+        if (col >= a.N) col = 0;
+        ops.pb[I] = W + (size_t)r * a.ldw + col;
+      }
+    }
+  };
+
+  // ---- open the first two tiles
+  S2STile lt{-1, -1, 0, 0, 0, 0};
+  if (!next_tile(lt)) return;
+  S2STile ct = lt;             // the multiplying side starts on the same tile
+  S2STile upcoming = lt;       // tile the loader will open next
+  bool have_upcoming = next_tile(upcoming);
+  fetch_rows(lt);
+  if (have_upcoming) fetch_rows(upcoming);
+  wait_loads<0>();
+  __syncthreads();
+  setup_pointers(lt);
+  ops.step = 0;
+  bool loader_live = true;
+  // loader moves one slot on; at a tile end it opens the upcoming tile and requests the rows of the one after
+  auto advance_loader = [&]() {
+    if (!loader_live) return;
+    if (++ops.step < nh) return;
+    if (!have_upcoming) {
+      loader_live = false;
+      ops.step = nh - 1;      // slots past the end repeat the last stage's addresses
+      return;
+    }
+    lt = upcoming;
+    ops.step = 0;
+    have_upcoming = next_tile(upcoming);
+    if (have_upcoming) fetch_rows(upcoming);
+    setup_pointers(lt);
+  };
+
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
+  char *patch = smem + RING_BYTES + wave * EPI_WAVE_BYTES;
+#pragma unroll 1
+  for (int st = 0; st < NSTAGE - 1; ++st) {
+#pragma unroll
+    for (int I = 0; I < 2 * NLD; ++I) ops.load(I, lds0 + st * STAGE_BYTES + (I / NLD) * TILE_BYTES);
+    advance_loader();
+  }
+  wait_loads<2 * NLD>();
+  __syncthreads();
+  bf16x8 fa[2][FR], fb[2][FR];
+  f32x16 acc[FR][FR];
+#pragma unroll
+  for (int i = 0; i < FR; ++i) fa[0][i] = ops.frag_a(smem, wm * (TB / 2) + i * 32, 0, lane);
+#pragma unroll
+  for (int j = 0; j < FR; ++j) fb[0][j] = ops.frag_b(smem + TILE_BYTES, wn * (TB / 2) + j * 32, 0, lane);
+
+  int g = 0;   // slot counter: slot g lives in stage g & 3
+  auto open_slot = [&]() {
+    wait_loads<2 * NLD>();   // stage g+1 has landed for every wavefront, stage g-1 is free
+    __syncthreads();
+  };
+  auto one_slot = [&](auto first) {
+    const char *cur = smem + (g & 3) * STAGE_BYTES;
+    const char *nxt = smem + ((g + 1) & 3) * STAGE_BYTES;
+    const uint32_t fill = lds0 + ((g + 3) & 3) * STAGE_BYTES;
+    half_step<decltype(first)::value>(ops, cur, nxt, fill, wm, wn, lane, fa, fb, acc);
+    advance_loader();
+    ++g;
+  };
+  open_slot();
+  for (;;) {   // one tile per trip; its first slot has been opened already
+    one_slot(std::true_type{});
+    for (int h = 1; h < nh; ++h) {
+      open_slot();
+      one_slot(std::false_type{});
+    }
+    // The next tile's first slot is opened before the epilogue: stores share the load counter,
+    // so this wait would otherwise also sit out the acknowledgement of every store below.
+    open_slot();
+    const int *idx = &s_idx[ct.ord % 3][wm * (TB / 2)];
+    const int rbase = ct.row0 + wm * (TB / 2);
+    auto dst_row = [&](int r) -> int {
+      int i = rbase + r;
+      int row = SCATTER_OUT ? idx[r] : i;
+      return (i < ct.row_end) ? row : -1;
+    };
+    store_wave_tile(acc, patch, dst_row, (bf16_t *)a.C, a.N, ct.n0 + wn * (TB / 2), a.N, lane);
+    if (!next_tile(ct)) break;
+  }
+  wait_loads<0>();
+}
+
+template <typename K> int set_lds_limit(K kernel, int bytes) {
+  return hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess
+             ? SMOE_OK
+             : SMOE_ERR_HIP;
+}
+
+uint32_t division_magic(int fan) { return fan > 1 ? (uint32_t)((0x100000000ULL + fan - 1) / fan) : 0u; }
+
+template <bool TRANS_W, bool SCATTER_OUT> int launch_s2s_stream_cfg(hipStream_t s, const S2SArgs &a) {
+  static int attr_rc = set_lds_limit(s2s_stream_kernel<TRANS_W, SCATTER_OUT>, STREAM_LDS_BYTES);
+  if (attr_rc != SMOE_OK) return attr_rc;
+  int tiles_n = ceil_div(a.N, TB);
+  int tiles_m = ceil_div(a.Tk, TB) + a.E;     // upper bound on sum_e ceil(n_e / 256)
+  int group_m = 4;
+  long long total = (long long)ceil_div(tiles_m, group_m) * group_m * tiles_n;
+  if (total > 0x7fffffffLL) return SMOE_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL((s2s_stream_kernel<TRANS_W, SCATTER_OUT>), dim3(STREAM_GRID), dim3(NTHREADS), STREAM_LDS_BYTES, s, a, tiles_n,
+                     group_m, (int)total, division_magic(a.a_map.o ? a.a_map.fan : 1));
+  SMOE_LAUNCH_CHECK();
+  return SMOE_OK;
+}
+
+}  // namespace
+
+// The persistent kernel keeps three half-steps in flight across tile boundaries, so a tile must
+// have at least three; the expert offsets must fit their LDS cache; order indices are divided
+// by the fan-out with a multiply-high that is exact while Tk * fan < 2^32.
+bool s2s_stream_supported(const S2SArgs &a) {
+  long long fan = a.a_map.o ? a.a_map.fan : 1;
+  return a.K % HK == 0 && a.K >= 3 * HK && a.N % 8 == 0 && a.ldw % 8 == 0 && a.Tk > 0 && a.E <= MAX_E &&
+         (long long)a.Tk * fan < 0x100000000LL;
+}
+
+int launch_s2s_stream(hipStream_t s, const S2SArgs &a) {
+  const bool scatter_out = a.c_map.o != nullptr;
+  if (a.trans_w) return scatter_out ? launch_s2s_stream_cfg<true, true>(s, a) : launch_s2s_stream_cfg<true, false>(s, a);
+  return scatter_out ? launch_s2s_stream_cfg<false, true>(s, a) : launch_s2s_stream_cfg<false, false>(s, a);
+}
