@@ -21,6 +21,7 @@ int run_s2s(smoe_ctx *ctx, hipStream_t s, smoe_dtype dt, const S2SArgs &a) {
   return launch_s2s_plain(s, dt, a);
 }
 int run_dw(smoe_ctx *ctx, hipStream_t s, smoe_dtype dt, const DWArgs &a) {
+  if (dt == SMOE_BF16 && ctx->kernel_mode == 0 && dw_stream_supported(a)) return launch_dw_stream(s, a);
   if (dt == SMOE_BF16 && ctx->kernel_mode != 1 && dw_mfma_supported(a)) return launch_dw_mfma(s, a, ctx->num_cu);
   return launch_dw_plain(s, dt, a);
 }
@@ -143,23 +144,24 @@ int smoe_plinear_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *
 }
 
 // ------------------------------------------------------------------------------ Alg. 2
-// Workspace: [dYbar: Tk x d_out, only if dY arrives scattered with gates]
-//            [dXbar: Tk x d_in, only if X was scattered with fan-out > 1]
-static void plinear_bwd_layout(smoe_dtype dt, int d_in, int d_out, int Tk, int k, int has_gates, int grouped_in,
-                               size_t &off_dybar, size_t &off_dxbar, size_t &total) {
+// Workspace: [dYbar: Tk x d_out, when dY arrives scattered (weighted or not) -- Alg. 2's group(dY, o, p)]
+//            [Xbar:  Tk x d_in, when X was scattered -- Alg. 2's group(X, o); the same array then
+//                    receives dXbar, the reuse Sec. 3.2.1 points out]
+static void plinear_bwd_layout(smoe_dtype dt, int d_in, int d_out, int Tk, int grouped_in, int grouped_out,
+                               size_t &off_dybar, size_t &off_xbar, size_t &total) {
   size_t es = dtype_size(dt), off = 0;
-  off_dybar = off_dxbar = (size_t)-1;
-  if (has_gates) { off_dybar = off; off += align256((size_t)Tk * d_out * es); }
-  if (!grouped_in && k > 1) { off_dxbar = off; off += align256((size_t)Tk * d_in * es); }
+  off_dybar = off_xbar = (size_t)-1;
+  if (!grouped_out) { off_dybar = off; off += align256((size_t)Tk * d_out * es); }
+  if (!grouped_in) { off_xbar = off; off += align256((size_t)Tk * d_in * es); }
   total = off;
 }
 
 size_t smoe_plinear_bwd_workspace_bytes(smoe_dtype dtype, int x_rows, int d_in, int d_out, int Tk, int k,
                                         int has_gates, int grouped_in, int grouped_out) {
-  (void)x_rows; (void)grouped_out;
-  if (!dtype_ok(dtype) || d_in < 1 || d_out < 1 || Tk < 0 || k < 1) return 0;
+  (void)x_rows; (void)k; (void)has_gates;
+  if (!dtype_ok(dtype) || d_in < 1 || d_out < 1 || Tk < 0) return 0;
   size_t a, b, total;
-  plinear_bwd_layout(dtype, d_in, d_out, Tk, k, has_gates, grouped_in, a, b, total);
+  plinear_bwd_layout(dtype, d_in, d_out, Tk, grouped_in, grouped_out, a, b, total);
   return total;
 }
 
@@ -176,14 +178,14 @@ int smoe_plinear_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *
   if (dgates && !Yhat) return SMOE_ERR_INVALID_ARG;
   if (!width_ok(dtype, d_in) || !width_ok(dtype, d_out)) return SMOE_ERR_UNSUPPORTED;
   if (!W && dX) return SMOE_ERR_INVALID_ARG;
-  size_t off_dybar, off_dxbar, need;
-  plinear_bwd_layout(dtype, d_in, d_out, Tk, k, gates != nullptr, grouped_in, off_dybar, off_dxbar, need);
+  size_t off_dybar, off_xbar, need;
+  plinear_bwd_layout(dtype, d_in, d_out, Tk, grouped_in, grouped_out, off_dybar, off_xbar, need);
   if (need && (!ws || ((uintptr_t)ws & 255) || ws_bytes < need)) return SMOE_ERR_WORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   int rc = SMOE_OK;
   if (Tk == 0) {  // no routed rows: dW is all zeros, nothing else to write
     if (dW) {
-      DWArgs z{nullptr, nullptr, dW, RowMap{nullptr, 1}, RowMap{nullptr, 1}, r->expert_offsets, r->E, 0, d_in, d_out};
+      DWArgs z{nullptr, nullptr, dW, r->expert_offsets, r->E, 0, d_in, d_out};
       rc = launch_dw_plain(s, dtype, z);
     }
     return rc;
@@ -192,38 +194,37 @@ int smoe_plinear_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *
   if (!aligned16(dY) || !aligned16(X) || (W && !aligned16(W)) || (dX && !aligned16(dX)) || (dW && !aligned16(dW)))
     return SMOE_ERR_UNSUPPORTED;
 
-  // dp = bmm(dY, Yhat), then the weighted group of dY (Alg. 2, first branch).
-  const void *dYsrc = dY;          // rows feeding the two GEMMs
-  bool dy_grouped = grouped_out != 0;
-  int dy_fan = 1;
-  if (gates) {
-    if (dgates) {
+  // dp = bmm(dY, Yhat); dYbar = group(dY, o, p)  (Alg. 2: "weight and group")
+  const void *dYbar = dY;
+  if (!grouped_out) {
+    if (gates && dgates) {
       rc = launch_rowdot(s, dtype, dY, Yhat, dgates, Tk, gates_k, d_out);
       if (rc != SMOE_OK) return rc;
     }
-    void *dYbar = (char *)ws + off_dybar;
-    rc = launch_group(s, dtype, dY, r->sorted_scattered_idxs, gates_k, gates, dYbar, Tk, d_out);
+    void *buf = (char *)ws + off_dybar;
+    rc = launch_group(s, dtype, dY, r->sorted_scattered_idxs, gates ? gates_k : 1, gates, buf, Tk, d_out);
     if (rc != SMOE_OK) return rc;
-    dYsrc = dYbar;
-    dy_grouped = true;
+    dYbar = buf;
   }
-  // dW = groupXTY(Xbar, dYbar); X and an unweighted scattered dY are gathered by the kernel
-  // itself instead of being copied into grouped order first.
+  // Xbar = group(X, o);  dW = groupXTY(Xbar, dYbar)
+  void *xbar = grouped_in ? nullptr : (void *)((char *)ws + off_xbar);
   if (dW) {
-    DWArgs a;
-    a.A = X; a.B = dYsrc; a.dW = dW;
-    a.a_map = RowMap{grouped_in ? nullptr : r->sorted_scattered_idxs, k};
-    a.b_map = RowMap{dy_grouped ? nullptr : r->sorted_scattered_idxs, dy_fan};
-    a.offsets = r->expert_offsets;
-    a.E = r->E; a.Tk = Tk; a.M = d_in; a.N = d_out;
+    const void *Xg = X;
+    if (!grouped_in) {
+      rc = launch_group(s, dtype, X, r->sorted_scattered_idxs, k, nullptr, xbar, Tk, d_in);
+      if (rc != SMOE_OK) return rc;
+      Xg = xbar;
+    }
+    DWArgs a{Xg, dYbar, dW, r->expert_offsets, r->E, Tk, d_in, d_out};
     rc = run_dw(ctx, s, dtype, a);
     if (rc != SMOE_OK) return rc;
   }
-  // dXbar = scatter2scatter(dYbar, W^T, o, 1): grouped or scattered like the forward input.
+  // dXbar = scatter2scatter(dYbar, W^T, o, 1): grouped or scattered like the forward input;
+  // with fan-out k the k slot gradients of a row are then summed.
   if (dX) {
     bool need_sum = !grouped_in && k > 1;
-    void *dst = need_sum ? (void *)((char *)ws + off_dxbar) : dX;
-    S2SArgs a = make_s2s(dYsrc, W, dst, r, d_in, d_out, true, dy_grouped, dy_fan, grouped_in != 0);
+    void *dst = need_sum ? xbar : dX;   // Xbar is dead once dW is done
+    S2SArgs a = make_s2s(dYbar, W, dst, r, d_in, d_out, true, true, 1, grouped_in != 0);
     rc = run_s2s(ctx, s, dtype, a);
     if (rc != SMOE_OK) return rc;
     if (need_sum) rc = launch_combine(s, dtype, dst, nullptr, dX, x_rows, k, d_in);
@@ -306,10 +307,10 @@ int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
   hipStream_t s = (hipStream_t)stream;
   int rc;
   if (T == 0) {
-    DWArgs z1{nullptr, nullptr, dW1, RowMap{nullptr, 1}, RowMap{nullptr, 1}, r->expert_offsets, r->E, 0, d_model, d_h};
+    DWArgs z1{nullptr, nullptr, dW1, r->expert_offsets, r->E, 0, d_model, d_h};
     rc = launch_dw_plain(s, dtype, z1);
     if (rc != SMOE_OK) return rc;
-    DWArgs z2{nullptr, nullptr, dW2, RowMap{nullptr, 1}, RowMap{nullptr, 1}, r->expert_offsets, r->E, 0, d_expert, d_model};
+    DWArgs z2{nullptr, nullptr, dW2, r->expert_offsets, r->E, 0, d_expert, d_model};
     return launch_dw_plain(s, dtype, z2);
   }
   if (!dY || !X || !W1 || !W2 || !gates || !saved_Hpre || !saved_H || !saved_Yhat || !dX || !dgates)
@@ -321,17 +322,14 @@ int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
   void *dYbar = p;                 p += align256((size_t)Tk * d_model * es);
   void *dH = p;                    p += align256((size_t)Tk * d_expert * es);
   void *dHpre = p;
-  void *dXbar = dYbar;  // dYbar is dead once dH and dW2 are done
+  void *Xbar = dYbar;  // dYbar is dead once dH and dW2 are done; its array then holds Xbar, then dXbar
 
   // ---- second ParallelLinear (grouped in, scattered weighted out)
   rc = launch_rowdot(s, dtype, dY, saved_Yhat, dgates, Tk, k, d_model);                 // dp = bmm(dY, Yhat)
   if (rc != SMOE_OK) return rc;
   rc = launch_group(s, dtype, dY, r->sorted_scattered_idxs, k, gates, dYbar, Tk, d_model);  // weight and group
   if (rc != SMOE_OK) return rc;
-  DWArgs w2;
-  w2.A = saved_H; w2.B = dYbar; w2.dW = dW2;
-  w2.a_map = RowMap{nullptr, 1}; w2.b_map = RowMap{nullptr, 1};
-  w2.offsets = r->expert_offsets; w2.E = r->E; w2.Tk = Tk; w2.M = d_expert; w2.N = d_model;
+  DWArgs w2{saved_H, dYbar, dW2, r->expert_offsets, r->E, Tk, d_expert, d_model};
   rc = run_dw(ctx, s, dtype, w2);                                                      // groupXTY
   if (rc != SMOE_OK) return rc;
   S2SArgs x2 = make_s2s(dYbar, W2, dH, r, d_expert, d_model, true, true, 1, true);      // dH = dYbar W2^T
@@ -340,22 +338,20 @@ int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
   // ---- activation
   rc = launch_act_bwd(s, dtype, act, saved_Hpre, dH, dHpre, Tk, d_expert);
   if (rc != SMOE_OK) return rc;
-  // ---- first ParallelLinear (scattered in with fan-out k, grouped out): X rows are
-  //      gathered inside groupXTY, so no grouped copy of X is made.
-  DWArgs w1;
-  w1.A = X; w1.B = dHpre; w1.dW = dW1;
-  w1.a_map = RowMap{r->sorted_scattered_idxs, k}; w1.b_map = RowMap{nullptr, 1};
-  w1.offsets = r->expert_offsets; w1.E = r->E; w1.Tk = Tk; w1.M = d_model; w1.N = d_h;
+  // ---- first ParallelLinear (scattered in with fan-out k, grouped out): its one `group`
+  rc = launch_group(s, dtype, X, r->sorted_scattered_idxs, k, nullptr, Xbar, Tk, d_model);
+  if (rc != SMOE_OK) return rc;
+  DWArgs w1{Xbar, dHpre, dW1, r->expert_offsets, r->E, Tk, d_model, d_h};
   rc = run_dw(ctx, s, dtype, w1);
   if (rc != SMOE_OK) return rc;
   if (k == 1) {  // slot id == token id: scatter straight into dX
     S2SArgs x1 = make_s2s(dHpre, W1, dX, r, d_model, d_h, true, true, 1, false);
     return run_s2s(ctx, s, dtype, x1);
   }
-  S2SArgs x1 = make_s2s(dHpre, W1, dXbar, r, d_model, d_h, true, true, 1, false);       // grouped -> scattered
+  S2SArgs x1 = make_s2s(dHpre, W1, Xbar, r, d_model, d_h, true, true, 1, false);        // grouped -> scattered dXbar
   rc = run_s2s(ctx, s, dtype, x1);
   if (rc != SMOE_OK) return rc;
-  return launch_combine(s, dtype, dXbar, nullptr, dX, T, k, d_model);                   // sum the k slots
+  return launch_combine(s, dtype, Xbar, nullptr, dX, T, k, d_model);                    // sum the k slots
 }
 
 }  // extern "C"

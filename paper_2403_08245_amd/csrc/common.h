@@ -70,11 +70,10 @@ struct S2SArgs {      // C[out(i), :] = A[in(i), :] * op(W[e(i)])   for sorted r
   size_t w_stride;    // elements between experts (= d_in * d_out)
   int trans_w;        // 0: op(W) = W (K = d_in, N = d_out); 1: op(W) = W^T (K = d_out, N = d_in)
 };
-struct DWArgs {       // dW[e] = sum_{i in segment e} A[a(i), :]^T B[b(i), :]
-  const void *A;      // [*, M]
-  const void *B;      // [*, N]
+struct DWArgs {       // dW[e] = sum_{i in segment e} A[i, :]^T B[i, :]   (both operands expert-sorted)
+  const void *A;      // [Tk, M]
+  const void *B;      // [Tk, N]
   void *dW;           // [E, M, N]
-  RowMap a_map, b_map;
   const int32_t *offsets;
   int E, Tk, M, N;
 };
@@ -87,3 +86,5 @@ int launch_dw_mfma(hipStream_t s, const DWArgs &a, int num_cu);
 // persistent tile-stream kernels (gemm_stream.hip)
 bool s2s_stream_supported(const S2SArgs &a);
 int launch_s2s_stream(hipStream_t s, const S2SArgs &a);
+bool dw_stream_supported(const DWArgs &a);
+int launch_dw_stream(hipStream_t s, const DWArgs &a);

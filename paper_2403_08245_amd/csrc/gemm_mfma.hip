@@ -4,7 +4,7 @@
 //     grouped or scattered.  The grouped copy of the input never exists in HBM: the gather
 //     happens in the global->LDS load, the "padded tile" of Sec. 3.1 lives only in LDS.
 //   * groupXTY (Sec. 3.2.1): dW[e] = Xbar_e^T dYbar_e over the expert's variable-length row
-//     segment, the token rows again gathered on the fly.
+//     segment of the two grouped operands.
 //
 // Shape of every kernel: 256 threads = 4 wavefronts in a 2x2 grid over a 256x256 output tile
 // (one wavefront per SIMD, 256 fp32 accumulator registers each), v_mfma_f32_32x32x16_bf16.
@@ -233,47 +233,24 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_mfma_kernel(S2SArgs a, int ti
 }
 
 // ======================================================================================
-// groupXTY: dW[e][m0:m0+256, n0:n0+256] = sum over the expert's rows i of A[amap(i), m]^T B[bmap(i), n]
+// groupXTY: dW[e][m0:m0+256, n0:n0+256] = sum over the expert's rows i of A[i, m]^T B[i, n]
 // ======================================================================================
-// Source-row numbers of a gathered operand come from the order indices.  Each wavefront keeps
-// a private ring of them in LDS, filled five half-steps ahead by a 4-byte direct-to-LDS load
-// (lanes 0..31: operand A rows of the step, lanes 32..63: operand B rows), so the gathered
-// tile loads never wait on an index lookup and all loads stay on one in-order counter.
-template <bool GATHER> struct DWOps {
-  static constexpr int EXTRA_LOADS = GATHER ? 1 : 0;
+// Both operands are in expert-sorted order (Alg. 2 groups them first); rows past the segment
+// read a block of zeros so they add nothing to the sum.
+struct DWOps {
+  static constexpr int EXTRA_LOADS = 0;
   const bf16_t *A, *B;
-  const int32_t *oa, *ob;      // order indices per operand or nullptr (rows already grouped)
-  uint32_t magic_a, magic_b;   // ceil(2^32 / fan), 0 when fan == 1
-  int M, N, lo, hi, max_i;
-  int ra[NLD], ca[NLD], rb[NLD], cb[NLD];  // per load instruction: row within the step, column offset
-  int uwave, lane;
-  uint32_t ring_lds;           // LDS byte address of this wavefront's ring [8 slots][64]
-  const int *ring;
+  int M, N, lo, hi;
+  int ra[NLD], ca[NLD], cb[NLD];  // per load instruction: row within the step, column offsets
+  int uwave;
   const bf16_t *pa[NLD], *pb[NLD];
 
-  __device__ __forceinline__ void fetch_indices(int step) {   // one 4-byte load per lane
-    int i = min(lo + step * HK + (lane & 31), max_i);
-    const int32_t *src = (lane < 32) ? (oa ? oa : ob) : (ob ? ob : oa);
-    load4_to_lds(src + i, ring_lds + (step & 7) * 256);
-  }
-  __device__ __forceinline__ int source_row(const int32_t *o, uint32_t magic, int step, int r, int half) {
-    int i = lo + step * HK + r;
-    if (i >= hi) return -1;
-    if (!GATHER || !o) return i;
-    uint32_t raw = (uint32_t)ring[(step & 7) * 64 + half * 32 + r];
-    return (int)(magic ? __umulhi(raw, magic) : raw);
-  }
   __device__ __forceinline__ void begin_group(int step) {
-    if (GATHER) fetch_indices(step + 2);   // consumed two groups later
 #pragma unroll
     for (int I = 0; I < NLD; ++I) {
-      int row = source_row(oa, magic_a, step, ra[I], 0);
-      pa[I] = (row >= 0) ? A + (size_t)row * M + ca[I] : (const bf16_t *)g_zero16;
-    }
-#pragma unroll
-    for (int I = 0; I < NLD; ++I) {
-      int row = source_row(ob, magic_b, step, rb[I], 1);
-      pb[I] = (row >= 0) ? B + (size_t)row * N + cb[I] : (const bf16_t *)g_zero16;
+      int i = lo + step * HK + ra[I];
+      pa[I] = (i < hi) ? A + (size_t)i * M + ca[I] : (const bf16_t *)g_zero16;
+      pb[I] = (i < hi) ? B + (size_t)i * N + cb[I] : (const bf16_t *)g_zero16;
     }
   }
   __device__ __forceinline__ void load(int I, int, uint32_t tile_lds) {
@@ -284,13 +261,10 @@ template <bool GATHER> struct DWOps {
   __device__ __forceinline__ bf16x8 frag_b(const char *tile, int base, int kk, int l) { return tr_frag(tile, base, kk, l); }
 };
 
-template <bool GATHER>
-__global__ void __launch_bounds__(NTHREADS, 1) dw_mfma_kernel(DWArgs a, int tiles_m, int tiles_n, uint32_t magic_a,
-                                                              uint32_t magic_b) {
+__global__ void __launch_bounds__(NTHREADS, 1) dw_mfma_kernel(DWArgs a, int tiles_m, int tiles_n) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   __shared__ int s_expert;
   __shared__ int s_rows[TB];
-  __shared__ int s_ring[4][8][64];
 
   // Block ids map to tiles directly: consecutive blocks (dealt round-robin to the XCDs) share
   // an expert, so every XCD gets the same mix of long and short contractions.
@@ -315,39 +289,24 @@ __global__ void __launch_bounds__(NTHREADS, 1) dw_mfma_kernel(DWArgs a, int tile
   const int wm = wave >> 1, wn = wave & 1;
   s_rows[threadIdx.x] = (m0 + (int)threadIdx.x < a.M) ? m0 + (int)threadIdx.x : -1;
 
-  DWOps<GATHER> ops;
+  DWOps ops;
   ops.A = (const bf16_t *)a.A;
   ops.B = (const bf16_t *)a.B;
-  ops.oa = a.a_map.o;
-  ops.ob = a.b_map.o;
-  ops.magic_a = magic_a;
-  ops.magic_b = magic_b;
   ops.M = a.M;
   ops.N = a.N;
   ops.lo = a.offsets[e];
   ops.hi = a.offsets[e + 1];
-  ops.max_i = a.Tk - 1;
   ops.uwave = __builtin_amdgcn_readfirstlane(wave);
-  ops.lane = lane;
-  ops.ring = &s_ring[wave][0][0];
-  ops.ring_lds = __builtin_amdgcn_readfirstlane(lds_address((const char *)&s_ring[wave][0][0]));
 #pragma unroll
   for (int I = 0; I < NLD; ++I) {
     int c;
     tr_lane_slot(wave, lane, I, ops.ra[I], c);
     ops.ca[I] = m0 + c * 8;
     if (ops.ca[I] >= a.M) ops.ca[I] = 0;
-    tr_lane_slot(wave, lane, I, ops.rb[I], c);
     ops.cb[I] = n0 + c * 8;
     if (ops.cb[I] >= a.N) ops.cb[I] = 0;
   }
   const int nh = (ops.hi - ops.lo + HK - 1) / HK;
-  if (GATHER && nh > 0) {   // the first three groups' row numbers must be in the ring before the loop resolves them
-    ops.fetch_indices(0);
-    ops.fetch_indices(1);
-    ops.fetch_indices(2);
-    wait_loads<0>();
-  }
 
   f32x16 acc[FR][FR];
   contraction_loop(ops, nh, smem, wm, wn, lane, acc);
@@ -378,17 +337,13 @@ template <bool TRANS_W> int launch_s2s_cfg(hipStream_t s, const S2SArgs &a) {
   return SMOE_OK;
 }
 
-// ceil(2^32 / fan): umulhi(x, magic) == x / fan whenever x * fan < 2^32
-uint32_t division_magic(int fan) { return fan > 1 ? (uint32_t)((0x100000000ULL + fan - 1) / fan) : 0u; }
-
-template <bool GATHER> int launch_dw_cfg(hipStream_t s, const DWArgs &a) {
-  static int attr_rc = set_lds_limit(dw_mfma_kernel<GATHER>, LDS_BYTES);
+int launch_dw_impl(hipStream_t s, const DWArgs &a) {
+  static int attr_rc = set_lds_limit(dw_mfma_kernel, LDS_BYTES);
   if (attr_rc != SMOE_OK) return attr_rc;
   int tiles_m = ceil_div(a.M, TB), tiles_n = ceil_div(a.N, TB);
   long long total = (long long)a.E * tiles_m * tiles_n;
   if (total > 0x7fffffffLL) return SMOE_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL((dw_mfma_kernel<GATHER>), dim3((unsigned)total), dim3(NTHREADS), LDS_BYTES, s, a, tiles_m,
-                     tiles_n, division_magic(a.a_map.o ? a.a_map.fan : 1), division_magic(a.b_map.o ? a.b_map.fan : 1));
+  hipLaunchKernelGGL(dw_mfma_kernel, dim3((unsigned)total), dim3(NTHREADS), LDS_BYTES, s, a, tiles_m, tiles_n);
   SMOE_LAUNCH_CHECK();
   return SMOE_OK;
 }
@@ -398,13 +353,7 @@ template <bool GATHER> int launch_dw_cfg(hipStream_t s, const DWArgs &a) {
 // The matrix-core kernels take contraction lengths that are multiples of 32 (no zero fill
 // along k) and widths that are multiples of 8 (16-byte chunks never straddle a row end).
 bool s2s_mfma_supported(const S2SArgs &a) { return a.K % HK == 0 && a.N % 8 == 0 && a.ldw % 8 == 0 && a.Tk > 0; }
-// groupXTY divides order indices by the fan-out with a multiply-high, exact while Tk * fan < 2^32.
-bool dw_mfma_supported(const DWArgs &a) {
-  long long fan = 1;
-  if (a.a_map.o && a.a_map.fan > fan) fan = a.a_map.fan;
-  if (a.b_map.o && a.b_map.fan > fan) fan = a.b_map.fan;
-  return a.M % 8 == 0 && a.N % 8 == 0 && a.Tk > 0 && (long long)a.Tk * fan < 0x100000000LL;
-}
+bool dw_mfma_supported(const DWArgs &a) { return a.M % 8 == 0 && a.N % 8 == 0 && a.Tk > 0; }
 
 int launch_s2s_mfma(hipStream_t s, const S2SArgs &a, int num_cu) {
   (void)num_cu;
@@ -413,5 +362,5 @@ int launch_s2s_mfma(hipStream_t s, const S2SArgs &a, int num_cu) {
 
 int launch_dw_mfma(hipStream_t s, const DWArgs &a, int num_cu) {
   (void)num_cu;
-  return (a.a_map.o || a.b_map.o) ? launch_dw_cfg<true>(s, a) : launch_dw_cfg<false>(s, a);
+  return launch_dw_impl(s, a);
 }

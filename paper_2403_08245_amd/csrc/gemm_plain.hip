@@ -96,8 +96,8 @@ __global__ void __launch_bounds__(256) dw_plain_kernel(DWArgs a) {
       int i = i0 + kk;
       float va = 0.f, vb = 0.f;
       if (i < hi) {
-        if (m0 + c < a.M) va = to_f32<T>(A[(size_t)map_row(a.a_map, i) * a.M + m0 + c]);
-        if (n0 + c < a.N) vb = to_f32<T>(B[(size_t)map_row(a.b_map, i) * a.N + n0 + c]);
+        if (m0 + c < a.M) va = to_f32<T>(A[(size_t)i * a.M + m0 + c]);
+        if (n0 + c < a.N) vb = to_f32<T>(B[(size_t)i * a.N + n0 + c]);
       }
       As[kk][c] = va;
       Bs[kk][c] = vb;

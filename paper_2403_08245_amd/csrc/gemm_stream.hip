@@ -8,7 +8,7 @@
 // what remains is the epilogue (accumulators -> bf16 -> LDS patch -> whole-line stores).
 //
 // Both sides visit the same sequence of slots (one per half-step, at least one per tile) with a
-// fixed lag.  Exactly eight tile loads (plus the index load of a gathered groupXTY) are issued
+// fixed lag.  Exactly eight tile loads are issued
 // per slot -- slots past the end of the list repeat a valid address -- so one constant
 // `s_waitcnt vmcnt` per slot orders everything.  Row indices travel through LDS by
 // direct-to-LDS loads as well: no ordinary global load sits in the loop, so the compiler never
@@ -107,14 +107,16 @@ __device__ __forceinline__ void half_step(Ops &ops, const char *cur, const char 
         fa[nkk][2] = ops.frag_a(src, wm * (TB / 2) + 2 * 32, nkk, lane);
         fa[nkk][3] = ops.frag_a(src, wm * (TB / 2) + 3 * 32, nkk, lane);
       }
+      // the source address of this group's load is worked out in the shadow of the matrix instructions
+      const int I = kk * FR + g;
+      const bf16_t *src_ptr = ops.prepare(I);
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
       }
       sched_fence();
-      const int I = kk * FR + g;
-      ops.load(I, fill + (I / NLD) * TILE_BYTES);
+      load16_to_lds(src_ptr, fill + (I / NLD) * TILE_BYTES + inst_off(ops.uwave, I % NLD));
       sched_fence();
     }
   }
@@ -134,9 +136,11 @@ template <bool TRANS_W> struct S2SStreamOps {
   size_t b_step;
   int step;                          // half-step the next loads fetch
   int uwave;
+  __device__ __forceinline__ const bf16_t *prepare(int I) const {
+    return I < NLD ? pa[I] + (size_t)step * HK : pb[I - NLD] + (size_t)step * b_step;
+  }
   __device__ __forceinline__ void load(int I, uint32_t tile_lds) {
-    if (I < NLD) load16_to_lds(pa[I] + (size_t)step * HK, tile_lds + inst_off(uwave, I));
-    else load16_to_lds(pb[I - NLD] + (size_t)step * b_step, tile_lds + inst_off(uwave, I - NLD));
+    load16_to_lds(prepare(I), tile_lds + inst_off(uwave, I % NLD));
   }
   __device__ __forceinline__ bf16x8 frag_a(const char *tile, int base, int kk, int lane) {
     return kc_frag(tile, base, kk, lane);
@@ -309,6 +313,192 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
   wait_loads<0>();
 }
 
+// ======================================================================================
+// groupXTY, persistent: dW[e] = Xbar_e^T dYbar_e over expert-sorted rows (Alg. 2 groups both
+// operands first; gathering the token rows inside this kernel measured a third slower than a
+// `group` copy followed by this kernel, the same ranking the paper reports).
+// ======================================================================================
+// The loader cursor runs three slots ahead of the multiplying cursor over the same slot
+// sequence: max(half-steps, 1) slots per tile, tiles in largest-expert-first order.  A tile of
+// an empty expert has one idle slot and writes zeros.
+struct DWCursor {
+  int seq;        // position in this block's tile list
+  int step, ns;   // slot within the tile, slots of the tile
+  int nh;         // half-steps (0 for an empty expert)
+  int e, lo, hi, m0, n0;
+  bool live;
+};
+
+struct DWStreamOps {
+  const bf16_t *A, *B;
+  int M, N;
+  int ra[NLD], ka[NLD];      // per load instruction: contraction row within a slot, 16-byte column chunk
+  int uwave;
+  // the loader's current slot (uniform)
+  int row_base, row_end, m0, n0;
+  bool real;
+  // Source address of load instruction I for the current slot; rows past the segment and idle
+  // slots read a block of zeros so they add nothing to the sum.
+  __device__ __forceinline__ const bf16_t *prepare(int I) const {
+    const int J = I % NLD;
+    const bool is_a = I < NLD;
+    int i = row_base + ra[J];
+    int col = (is_a ? m0 : n0) + ka[J] * 8;
+    if (col >= (is_a ? M : N)) col = 0;
+    const bf16_t *p = (is_a ? A : B) + (size_t)i * (is_a ? M : N) + col;
+    return (real && i < row_end) ? p : (const bf16_t *)g_zero16;
+  }
+  __device__ __forceinline__ void load(int I, uint32_t tile_lds) {
+    load16_to_lds(prepare(I), tile_lds + inst_off(uwave, I % NLD));
+  }
+  __device__ __forceinline__ bf16x8 frag_a(const char *tile, int base, int kk, int l) { return tr_frag(tile, base, kk, l); }
+  __device__ __forceinline__ bf16x8 frag_b(const char *tile, int base, int kk, int l) { return tr_frag(tile, base, kk, l); }
+};
+
+__global__ void __launch_bounds__(NTHREADS, 1) dw_stream_kernel(DWArgs a, int tiles_m, int tiles_n) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  __shared__ int s_off[MAX_E + 1];
+  __shared__ int s_order[MAX_E];      // experts, largest segment first
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int G = gridDim.x;
+  const int slot_in_round = ((int)blockIdx.x & 7) * (G >> 3) + ((int)blockIdx.x >> 3);  // XCD-contiguous tiles
+  const int per_expert = tiles_m * tiles_n;
+  const int group_m = (tiles_m % 8 == 0) ? 8 : ((tiles_m % 4 == 0) ? 4 : ((tiles_m % 2 == 0) ? 2 : 1));
+
+  for (int i = threadIdx.x; i <= a.E; i += NTHREADS) s_off[i] = a.offsets[i];
+  __syncthreads();
+  for (int x = threadIdx.x; x < a.E; x += NTHREADS) {
+    int nx = s_off[x + 1] - s_off[x], before = 0;
+    for (int y = 0; y < a.E; ++y) {
+      int ny = s_off[y + 1] - s_off[y];
+      before += (ny > nx) || (ny == nx && y < x);
+    }
+    s_order[before] = x;
+  }
+  __syncthreads();
+
+  auto open_tile = [&](DWCursor &c, int seq) {
+    c.seq = seq;
+    int T = seq * G + slot_in_round;
+    int rank = T / per_expert;
+    c.live = rank < a.E;
+    if (!c.live) return;
+    int t = T - rank * per_expert;
+    c.e = s_order[rank];
+    c.lo = s_off[c.e];
+    c.hi = s_off[c.e + 1];
+    // inside an expert: bands of group_m M-tiles, N-tile by N-tile, so that the 32 consecutive
+    // tiles an XCD holds at a time form a compact patch sharing few operand panels
+    int band = t / (group_m * tiles_n), r = t - band * (group_m * tiles_n);
+    c.m0 = (band * group_m + r % group_m) * TB;
+    c.n0 = (r / group_m) * TB;
+    c.nh = (c.hi - c.lo + HK - 1) / HK;
+    c.ns = max(c.nh, 1);
+    c.step = 0;
+  };
+  auto advance = [&](DWCursor &c) {
+    if (!c.live) return;
+    if (++c.step < c.ns) return;
+    open_tile(c, c.seq + 1);
+  };
+
+  DWStreamOps ops;
+  ops.uwave = __builtin_amdgcn_readfirstlane(wave);
+  ops.A = (const bf16_t *)a.A;
+  ops.B = (const bf16_t *)a.B;
+  ops.M = a.M;
+  ops.N = a.N;
+#pragma unroll
+  for (int I = 0; I < NLD; ++I) tr_lane_slot(wave, lane, I, ops.ra[I], ops.ka[I]);
+  // loader cursor: publish the slot whose eight loads are issued next
+  auto resolve = [&](const DWCursor &c) {
+    ops.real = c.live && c.nh > 0;
+    ops.row_base = c.lo + c.step * HK;
+    ops.row_end = c.hi;
+    ops.m0 = c.m0;
+    ops.n0 = c.n0;
+  };
+
+  DWCursor cc, lc;
+  open_tile(cc, 0);
+  if (!cc.live) return;
+  lc = cc;
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
+  char *patch = smem + RING_BYTES + wave * EPI_WAVE_BYTES;
+#pragma unroll 1
+  for (int st = 0; st < NSTAGE - 1; ++st) {
+    resolve(lc);
+#pragma unroll
+    for (int I = 0; I < 2 * NLD; ++I) ops.load(I, lds0 + st * STAGE_BYTES + (I / NLD) * TILE_BYTES);
+    advance(lc);
+  }
+  wait_loads<2 * NLD>();
+  __syncthreads();
+  bf16x8 fa[2][FR], fb[2][FR];
+  f32x16 acc[FR][FR];
+#pragma unroll
+  for (int i = 0; i < FR; ++i) fa[0][i] = ops.frag_a(smem, wm * (TB / 2) + i * 32, 0, lane);
+#pragma unroll
+  for (int j = 0; j < FR; ++j) fb[0][j] = ops.frag_b(smem + TILE_BYTES, wn * (TB / 2) + j * 32, 0, lane);
+
+  int g = 0;
+  auto open_slot = [&]() {
+    wait_loads<2 * NLD>();
+    __syncthreads();
+  };
+  auto one_slot = [&](auto first) {
+    const char *cur = smem + (g & 3) * STAGE_BYTES;
+    const char *nxt = smem + ((g + 1) & 3) * STAGE_BYTES;
+    const uint32_t fill = lds0 + ((g + 3) & 3) * STAGE_BYTES;
+    resolve(lc);
+    half_step<decltype(first)::value>(ops, cur, nxt, fill, wm, wn, lane, fa, fb, acc);
+    advance(lc);
+    ++g;
+  };
+  auto idle_slot = [&]() {   // tile of an empty expert: keep the loader and the load count going, result is zero
+    const uint32_t fill = lds0 + ((g + 3) & 3) * STAGE_BYTES;
+    const char *nxt = smem + ((g + 1) & 3) * STAGE_BYTES;
+    resolve(lc);
+#pragma unroll
+    for (int I = 0; I < 2 * NLD; ++I) ops.load(I, fill + (I / NLD) * TILE_BYTES);
+    advance(lc);
+#pragma unroll
+    for (int i = 0; i < FR; ++i)
+#pragma unroll
+      for (int j = 0; j < FR; ++j)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
+    // the fragments of the next slot were not prefetched by a multiplying slot: read them here
+#pragma unroll
+    for (int i = 0; i < FR; ++i) fa[0][i] = ops.frag_a(nxt, wm * (TB / 2) + i * 32, 0, lane);
+#pragma unroll
+    for (int j = 0; j < FR; ++j) fb[0][j] = ops.frag_b(nxt + TILE_BYTES, wn * (TB / 2) + j * 32, 0, lane);
+    ++g;
+  };
+  open_slot();
+  for (;;) {   // one tile per trip; its first slot has been opened already
+    if (cc.nh > 0) {
+      one_slot(std::true_type{});
+      for (int h = 1; h < cc.nh; ++h) {
+        open_slot();
+        one_slot(std::false_type{});
+      }
+    } else {
+      idle_slot();
+    }
+    open_slot();   // the next tile's first slot, before the stores below join the load counter
+    const int mbase = cc.m0 + wm * (TB / 2);
+    auto dst_row = [&](int r) -> int { return (mbase + r < a.M) ? mbase + r : -1; };
+    store_wave_tile(acc, patch, dst_row, (bf16_t *)a.dW + (size_t)cc.e * a.M * a.N, a.N, cc.n0 + wn * (TB / 2), a.N,
+                    lane);
+    open_tile(cc, cc.seq + 1);
+    if (!cc.live) break;
+  }
+  wait_loads<0>();
+}
+
 template <typename K> int set_lds_limit(K kernel, int bytes) {
   return hipFuncSetAttribute((const void *)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess
              ? SMOE_OK
@@ -331,6 +521,15 @@ template <bool TRANS_W, bool SCATTER_OUT> int launch_s2s_stream_cfg(hipStream_t 
   return SMOE_OK;
 }
 
+int launch_dw_stream_impl(hipStream_t s, const DWArgs &a) {
+  static int attr_rc = set_lds_limit(dw_stream_kernel, STREAM_LDS_BYTES);
+  if (attr_rc != SMOE_OK) return attr_rc;
+  int tiles_m = ceil_div(a.M, TB), tiles_n = ceil_div(a.N, TB);
+  hipLaunchKernelGGL(dw_stream_kernel, dim3(STREAM_GRID), dim3(NTHREADS), STREAM_LDS_BYTES, s, a, tiles_m, tiles_n);
+  SMOE_LAUNCH_CHECK();
+  return SMOE_OK;
+}
+
 }  // namespace
 
 // The persistent kernel keeps three half-steps in flight across tile boundaries, so a tile must
@@ -347,3 +546,10 @@ int launch_s2s_stream(hipStream_t s, const S2SArgs &a) {
   if (a.trans_w) return scatter_out ? launch_s2s_stream_cfg<true, true>(s, a) : launch_s2s_stream_cfg<true, false>(s, a);
   return scatter_out ? launch_s2s_stream_cfg<false, true>(s, a) : launch_s2s_stream_cfg<false, false>(s, a);
 }
+
+bool dw_stream_supported(const DWArgs &a) {
+  long long tiles = (long long)a.E * ceil_div(a.M, TB) * ceil_div(a.N, TB);
+  return a.M % 8 == 0 && a.N % 8 == 0 && a.Tk > 0 && a.E <= MAX_E && tiles + STREAM_GRID < 0x7fffffffLL;
+}
+
+int launch_dw_stream(hipStream_t s, const DWArgs &a) { return launch_dw_stream_impl(s, a); }
