@@ -35,9 +35,50 @@ __global__ void __launch_bounds__(256) topk_gate_kernel(const float *__restrict_
   for (int j = 0; j < k; ++j) gates[(size_t)t * k + j] *= inv;
 }
 
+// Same selection with one wavefront per token for E <= 64: lane e holds logit e, each of the k
+// rounds is a butterfly arg-max over (not yet taken, value descending, expert id ascending).
+__global__ void __launch_bounds__(256) topk_gate_wave_kernel(const float *__restrict__ logits, int T, int E, int k,
+                                                             int32_t *__restrict__ idx, float *__restrict__ gates) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  const bool has = lane < E;
+  float v = has ? logits[(size_t)t * E + lane] : 0.f;
+  bool avail = has;
+  float mine = 0.f, first_v = 0.f;   // lane j keeps the value picked in round j
+  int mine_i = -1;
+  for (int j = 0; j < k; ++j) {
+    float bv = v;
+    int bi = lane;
+    bool ba = avail;
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) {
+      float ov = __shfl_xor(bv, d, 64);
+      int oi = __shfl_xor(bi, d, 64);
+      bool oa = __shfl_xor((int)ba, d, 64) != 0;
+      bool other_wins = oa && (!ba || ov > bv || (ov == bv && oi < bi));
+      if (other_wins) { bv = ov; bi = oi; ba = true; }
+    }
+    if (j == 0) first_v = bv;
+    if (lane == j) { mine = bv; mine_i = bi; }
+    if (lane == bi) avail = false;
+  }
+  float w = (lane < k) ? expf(mine - first_v) : 0.f;
+  float sum = w;
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) sum += __shfl_xor(sum, d, 64);
+  if (lane < k) {
+    idx[(size_t)t * k + lane] = mine_i;
+    gates[(size_t)t * k + lane] = w * (1.0f / sum);
+  }
+}
+
 int launch_topk_gate(hipStream_t s, const float *logits, int T, int E, int k, int32_t *idx, float *gates) {
   if (T == 0) return SMOE_OK;
-  hipLaunchKernelGGL(topk_gate_kernel, dim3(ceil_div(T, 256)), dim3(256), 0, s, logits, T, E, k, idx, gates);
+  if (E <= 64)
+    hipLaunchKernelGGL(topk_gate_wave_kernel, dim3(ceil_div(T, 4)), dim3(256), 0, s, logits, T, E, k, idx, gates);
+  else
+    hipLaunchKernelGGL(topk_gate_kernel, dim3(ceil_div(T, 256)), dim3(256), 0, s, logits, T, E, k, idx, gates);
   SMOE_LAUNCH_CHECK();
   return SMOE_OK;
 }
@@ -68,14 +109,18 @@ __global__ void __launch_bounds__(64) route_count_kernel(const int32_t *__restri
   for (int e = threadIdx.x; e < E; e += 64) counts[(size_t)blockIdx.x * E + e] = hist[e];
 }
 
-// counts[c][e] -> start position of (c, e); offsets[e] = rows before expert e.
-__global__ void __launch_bounds__(256) route_scan_kernel(int32_t *__restrict__ counts, int nchunk, int E,
-                                                         int32_t *__restrict__ offsets, int Tk) {
+// counts[c][e] -> start position of (c, e); offsets[e] = rows before expert e.  One wavefront
+// per expert at a time: lanes take chunks, a wave prefix sum orders them.
+__global__ void __launch_bounds__(1024) route_scan_kernel(int32_t *__restrict__ counts, int nchunk, int E,
+                                                          int32_t *__restrict__ offsets, int Tk) {
   extern __shared__ int32_t totals[];  // [E] rows per expert, then exclusive prefix
-  for (int e = threadIdx.x; e < E; e += blockDim.x) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwave = blockDim.x >> 6;
+  for (int e = wave; e < E; e += nwave) {
     int sum = 0;
-    for (int c = 0; c < nchunk; ++c) sum += counts[(size_t)c * E + e];
-    totals[e] = sum;
+    for (int c = lane; c < nchunk; c += 64) sum += counts[(size_t)c * E + e];
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) sum += __shfl_xor(sum, d, 64);
+    if (lane == 0) totals[e] = sum;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -89,12 +134,19 @@ __global__ void __launch_bounds__(256) route_scan_kernel(int32_t *__restrict__ c
     offsets[E] = run;
   }
   __syncthreads();
-  for (int e = threadIdx.x; e < E; e += blockDim.x) {
+  for (int e = wave; e < E; e += nwave) {
     int run = totals[e];
-    for (int c = 0; c < nchunk; ++c) {
-      int n = counts[(size_t)c * E + e];
-      counts[(size_t)c * E + e] = run;
-      run += n;
+    for (int c0 = 0; c0 < nchunk; c0 += 64) {
+      int c = c0 + lane;
+      int n = (c < nchunk) ? counts[(size_t)c * E + e] : 0;
+      int incl = n;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        int up = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += up;
+      }
+      if (c < nchunk) counts[(size_t)c * E + e] = run + incl - n;
+      run += __shfl(incl, 63, 64);
     }
   }
 }
@@ -145,7 +197,7 @@ int launch_route(hipStream_t s, const int32_t *expert_idxs, int Tk, int E, int32
   size_t shm = (size_t)E * sizeof(int32_t);
   hipLaunchKernelGGL(route_count_kernel, dim3(nchunk), dim3(64), shm, s, expert_idxs, Tk, E, counts);
   SMOE_LAUNCH_CHECK();
-  hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(256), shm, s, counts, nchunk, E, offsets, Tk);
+  hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(1024), shm, s, counts, nchunk, E, offsets, Tk);
   SMOE_LAUNCH_CHECK();
   if (Tk > 0) {
     hipLaunchKernelGGL(route_place_kernel, dim3(nchunk), dim3(64), shm, s, expert_idxs, Tk, E, counts, sorted_e,

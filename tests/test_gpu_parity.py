@@ -139,10 +139,10 @@ def test_group_matches_definition(smoe):
 
 
 # ------------------------------------------------------------------ SMoE MLP, whole-tensor parity
-def _mlp_parity(smoe, cfg, seed, plain=False):
+def _mlp_parity(smoe, cfg, seed, plain=False, mode=None):
     td = torch_dtype(cfg.dtype)
     case = si.mlp_case(cfg, seed)
-    smoe.set_kernel_mode(1 if plain else 0)
+    smoe.set_kernel_mode(mode if mode is not None else (1 if plain else 0))
     try:
         gi, gg = smoe.topk_gate(case["logits"].cuda(), cfg.k)
         r = smoe.route(gi, cfg.E)
@@ -184,6 +184,21 @@ def test_mlp_reduced_mixtral_shape_full(smoe, name):
 
 def test_mlp_bf16_plain_kernels_full(smoe):
     _mlp_parity(smoe, si.CONFIGS["C3-small"], 2, plain=True)
+
+
+def test_mlp_bf16_one_block_per_tile_kernels_full(smoe):
+    """The non-persistent matrix-core kernels (fallback for short contractions / many experts)."""
+    _mlp_parity(smoe, si.CONFIGS["C3-small"], 3, mode=2)
+
+
+def test_mlp_more_experts_than_the_offset_cache(smoe):
+    cfg = si.custom("E300", T=700, d_model=128, d_expert=64, E=300, k=2, act=si.ACT_SWIGLU, dtype="bf16")
+    _mlp_parity(smoe, cfg, 8)
+
+
+def test_mlp_short_contraction_falls_back(smoe):
+    cfg = si.custom("K64", T=600, d_model=64, d_expert=32, E=4, k=2, act=si.ACT_GELU, dtype="bf16")
+    _mlp_parity(smoe, cfg, 9)
 
 
 @pytest.mark.parametrize("act", [si.ACT_NONE, si.ACT_GELU, si.ACT_SWIGLU])
