@@ -386,9 +386,9 @@ __global__ void __launch_bounds__(NTHREADS, 1) dw_stream_kernel(DWArgs a, int ti
     c.live = rank < a.E;
     if (!c.live) return;
     int t = T - rank * per_expert;
-    c.e = s_order[rank];
-    c.lo = s_off[c.e];
-    c.hi = s_off[c.e + 1];
+    c.e = __builtin_amdgcn_readfirstlane(s_order[rank]);   // LDS reads land in vector registers: make them scalar again
+    c.lo = __builtin_amdgcn_readfirstlane(s_off[c.e]);
+    c.hi = __builtin_amdgcn_readfirstlane(s_off[c.e + 1]);
     // inside an expert: bands of group_m M-tiles, N-tile by N-tile, so that the 32 consecutive
     // tiles an XCD holds at a time form a compact patch sharing few operand panels
     int band = t / (group_m * tiles_n), r = t - band * (group_m * tiles_n);

@@ -98,14 +98,16 @@ __device__ __forceinline__ bool locate_tile(const int32_t *offsets, int E, int t
       int up = __shfl_up(incl, d, 64);
       if (lane >= d) incl += up;
     }
-    int total = __shfl(incl, 63, 64);
+    // wave-uniform values are moved to scalar registers by hand so that the callers' control
+    // flow (tile bookkeeping of the persistent kernels) stays scalar as well
+    int total = __builtin_amdgcn_readfirstlane(__shfl(incl, 63, 64));
     if (tile < base + total) {
       unsigned long long owns = __ballot(base + incl > tile);
       int first = __ffsll((long long)owns) - 1;
-      int before = __shfl(incl - nt, first, 64);
+      int before = __builtin_amdgcn_readfirstlane(__shfl(incl - nt, first, 64));
       e = c0 + first;
-      row0 = __shfl(lo, first, 64) + (tile - base - before) * TB;
-      row_end = __shfl(hi, first, 64);
+      row0 = __builtin_amdgcn_readfirstlane(__shfl(lo, first, 64)) + (tile - base - before) * TB;
+      row_end = __builtin_amdgcn_readfirstlane(__shfl(hi, first, 64));
       return true;
     }
     base += total;
