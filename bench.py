@@ -173,7 +173,7 @@ def main():
         "ms_event_median": float(np.median(per_step)), "ms_event_p5": float(np.percentile(per_step, 5)),
         "ms_event_p95": float(np.percentile(per_step, 95)),
         "phases_ms": {"routing": ms_route, "mlp_fwd": ms_fwd, "mlp_bwd": ms_bwd},
-        "roofline": {"bound": "mfma", "kernel": "s2s_mfma_kernel (ParallelLinear #1, scattered->grouped)",
+        "roofline": {"bound": "mfma", "kernel": "s2s_stream_kernel<false,false> (ParallelLinear #1, scattered->grouped)",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "ms_per_launch": ms_s2s, "flop_per_launch": s2s_flops, "traffic": traffic},
     }

@@ -120,8 +120,10 @@ int smoe_plinear_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *
  *   dX     (out) same shape as X; with scattered input the k slot gradients of a row are summed.
  *   dW     (out) [E, d_in, d_out] in the weight dtype; zeros for experts with no rows.
  *   dgates (out, nullable) [Tk] fp32, dgates[s] = <dY[s / gates_k], Yhat[s]>.
- * Either of dX / dW may be NULL to skip it.  Steps: weighted group of dY (only when it is
- * scattered), groupXTY for dW, scatter2scatter with W^T for dX. */
+ * Either of dX / dW may be NULL to skip it.  Steps as in Alg. 2: dgates row dots, `group` of
+ * dY (weighted by the gates) and of X whenever they are not already expert-sorted, groupXTY
+ * for dW on the two grouped operands, scatter2scatter with W^T for dX, and the sum over a
+ * row's k slots when the input was scattered.  The workspace holds the grouped copies. */
 size_t smoe_plinear_bwd_workspace_bytes(smoe_dtype dtype, int x_rows, int d_in, int d_out, int Tk,
                                         int k, int has_gates, int grouped_in, int grouped_out);
 int smoe_plinear_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *dY, const void *X,
