@@ -61,6 +61,77 @@ def cpu_baseline(case, cfg, gates_np, ei_np, budget_s: float):
     }
 
 
+def granularity_sweep(args):
+    """Sec. 4.2: throughput of the SMoE MLP for k in {1,2,4,8,16} (E = 8k, d_expert = d_ff/k) relative to the
+    dense MLP with the same active parameters, run through the same library as one expert with k = 1.
+    Inputs are drawn on the GPU (timing only; parity at these shapes is covered by the GPU tests)."""
+    import smoe_inputs as si
+    import paper_2403_08245_amd as smoe
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream()
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(args.seed)
+
+    def draw(shape, std, dtype=torch.bfloat16):
+        return (torch.randn(*shape, generator=gen, device=dev, dtype=torch.float32) * std).to(dtype)
+
+    def run(cfg):
+        X, dY = draw((cfg.T, cfg.d_model), 1.0), draw((cfg.T, cfg.d_model), 1.0)
+        W1, W2 = draw((cfg.E, cfg.d_model, cfg.d_h), 0.02), draw((cfg.E, cfg.d_expert, cfg.d_model), 0.02)
+        logits = draw((cfg.T, cfg.E), 1.0, torch.float32)
+        buf = smoe.MLPBuffers(cfg.T, cfg.k, cfg.E, cfg.d_model, cfg.d_expert, cfg.act, torch.bfloat16, dev,
+                              training=True)
+
+        def fwd():
+            ei, gates = smoe.topk_gate(logits, cfg.k)
+            r = smoe.route(ei, cfg.E)
+            smoe.mlp_fwd(X, W1, W2, r, cfg.k, gates, cfg.act, buf)
+            return r, gates
+
+        def fwd_bwd():
+            r, gates = fwd()
+            smoe.mlp_bwd(dY, X, W1, W2, r, cfg.k, gates, cfg.act, buf)
+
+        out = {}
+        for name, fn in (("inference", fwd), ("training", fwd_bwd)):
+            for _ in range(args.warmup):
+                fn()
+            ev = _events(args.steps + 1)
+            ev[0].record(stream)
+            for i in range(args.steps):
+                fn()
+                ev[i + 1].record(stream)
+            torch.cuda.synchronize()
+            ts = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)])
+            flops = cfg.gemm_flops_fwd() * (1.0 if name == "inference" else 3.0)
+            out[name] = {"ms_median": float(np.median(ts)), "ms_p5": float(np.percentile(ts, 5)),
+                         "ms_p95": float(np.percentile(ts, 95)), "tflops": flops / (np.median(ts) * 1e-3) / 1e12,
+                         "tokens_per_s": cfg.T / (np.median(ts) * 1e-3)}
+        del X, dY, W1, W2, buf
+        torch.cuda.empty_cache()
+        return out
+
+    dense = run(si.CONFIGS["G-dense"])
+    rows = []
+    for k in si.GRANULARITY_KS:
+        cfg = si.CONFIGS[f"G{k}"]
+        res = run(cfg)
+        rows.append({"k": k, "E": cfg.E, "d_expert": cfg.d_expert, **res,
+                     "relative_throughput_training": dense["training"]["ms_median"] / res["training"]["ms_median"],
+                     "relative_throughput_inference": dense["inference"]["ms_median"] / res["inference"]["ms_median"]})
+    head = next(r for r in rows if r["k"] == 4)
+    print(json.dumps({
+        "metric": "SMoE MLP fwd+bwd GEMM throughput per layer, unit-benchmark shape E=32 k=4 (Sec. 4.1)",
+        "value": head["training"]["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": head["training"]["ms_median"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "granularity sweep: T=61440 d_model=4096 d_ff=8192 d_expert=d_ff/k E=8k act=gelu, "
+                               "uniform router"},
+        "dense_equal_active_parameters": dense, "sweep": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -72,11 +143,16 @@ def main():
     ap.add_argument("--kernel-reps", type=int, default=20)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB elementwise copy kernel (reference for the HBM byte counters)")
+    ap.add_argument("--sweep", choices=["granularity"], default=None,
+                    help="run the Sec. 4.2 granularity sweep instead of one workload (one JSON line with all points)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (data-parallel sharding is a design note); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+
+    if args.sweep == "granularity":
+        return granularity_sweep(args)
 
     import smoe_inputs as si
     import paper_2403_08245_amd as smoe

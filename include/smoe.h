@@ -89,6 +89,15 @@ int smoe_set_kernel_mode(smoe_ctx *ctx, int mode);
 int smoe_topk_gate(smoe_ctx *ctx, void *stream, const float *logits, int T, int E, int k,
                    int32_t *expert_idxs, float *gates);
 
+/* Gradient of the gate with respect to the router logits, closing the chain from Alg. 2's dp
+ * (dgates) to the router of Sec. 3.1 step 1: on a token's k kept experts
+ * dlogits[t,e_j] = g_j (dp_j - sum_i g_i dp_i), zero for every other expert (the selection is
+ * piecewise constant).
+ *   expert_idxs [T*k] int32, gates [T*k] fp32 (outputs of smoe_topk_gate), dgates [T*k] fp32 (in)
+ *   dlogits [T,E] fp32 (out, every entry written). */
+int smoe_topk_gate_bwd(smoe_ctx *ctx, void *stream, const int32_t *expert_idxs, const float *gates,
+                       const float *dgates, int T, int E, int k, float *dlogits);
+
 /* ---- routing: Sec. 3.1 step 2 -------------------------------------------------------
  * Stable bucket sort of the Tk = T*k slots by expert.  Outputs as in smoe_routing.
  * Integer work, bit-exact.  Experts nobody chose get an empty segment. */

@@ -46,7 +46,7 @@ from scipy.special import erf as _erf
 __all__ = [
     "ACT_NONE", "ACT_GELU", "ACT_SWIGLU",
     "act_fwd", "act_bwd", "hidden_width",
-    "topk_gate", "route",
+    "topk_gate", "topk_gate_bwd", "route",
     "plinear_fwd", "plinear_bwd",
     "mlp_token_fwd", "mlp_fwd", "mlp_token_bwd", "mlp_bwd",
     "mlp_dW2_rows", "mlp_dW1_cols",
@@ -123,6 +123,25 @@ def topk_gate(logits: np.ndarray, k: int):
         expert_idxs[t] = top
         gates[t] = w / w.sum()
     return expert_idxs, gates
+
+
+def topk_gate_bwd(expert_idxs: np.ndarray, gates: np.ndarray, dgates: np.ndarray, E: int) -> np.ndarray:
+    """Gradient of step 1 of Sec. 3.1 with respect to the router logits.
+
+    The gates of a token are the softmax of its k kept logits, so with g = gates[t] the Jacobian
+    on the kept experts is diag(g) - g g^T and every other expert has a zero gradient (the
+    selection itself is piecewise constant).  Takes Alg. 2's dp (dgates [T,k]) and returns
+    dlogits [T,E] float64.
+    """
+    expert_idxs = np.asarray(expert_idxs)
+    T, k = expert_idxs.shape
+    g = np.asarray(gates, dtype=np.float64).reshape(T, k)
+    dg = np.asarray(dgates, dtype=np.float64).reshape(T, k)
+    dlogits = np.zeros((T, E), dtype=np.float64)
+    for t in range(T):
+        jac = np.diag(g[t]) - np.outer(g[t], g[t])
+        dlogits[t, expert_idxs[t]] = jac @ dg[t]
+    return dlogits
 
 
 def route(expert_idxs: np.ndarray, E: int):

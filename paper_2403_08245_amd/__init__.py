@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(_PKG, "libsmoe.so")
 
 EXPORTS = [
     "smoe_create", "smoe_destroy", "smoe_strerror", "smoe_abi_version", "smoe_set_kernel_mode",
-    "smoe_topk_gate", "smoe_route_workspace_bytes", "smoe_route",
+    "smoe_topk_gate", "smoe_topk_gate_bwd", "smoe_route_workspace_bytes", "smoe_route",
     "smoe_plinear_fwd", "smoe_plinear_bwd_workspace_bytes", "smoe_plinear_bwd",
     "smoe_mlp_fwd_workspace_bytes", "smoe_mlp_fwd", "smoe_mlp_bwd_workspace_bytes", "smoe_mlp_bwd",
     "smoe_group",
@@ -31,7 +31,7 @@ EXPORTS = [
 def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(
-            f"{LIB_PATH} not found: build it first (python -m paper_2403_08245_amd.build); "
+            f"{LIB_PATH} not found: build it first (python __graft_entry__.py); "
             "this package has no fallback path")
     return ctypes.CDLL(LIB_PATH)
 
@@ -54,6 +54,7 @@ lib.smoe_strerror.argtypes = [_i]
 lib.smoe_strerror.restype = ctypes.c_char_p
 lib.smoe_set_kernel_mode.argtypes = [_vp, _i]
 lib.smoe_topk_gate.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp, _vp]
+lib.smoe_topk_gate_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp]
 lib.smoe_route_workspace_bytes.argtypes = [_i, _i, _i]
 lib.smoe_route_workspace_bytes.restype = _sz
 lib.smoe_route.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _sz]
@@ -147,6 +148,19 @@ def topk_gate(logits: torch.Tensor, k: int):
     gates = torch.empty(T, k, dtype=torch.float32, device=logits.device)
     _check(lib.smoe_topk_gate(ctx(), _stream(), _p(logits), T, E, k, _p(idx), _p(gates)), "smoe_topk_gate")
     return idx, gates
+
+
+def topk_gate_bwd(expert_idxs: torch.Tensor, gates: torch.Tensor, dgates: torch.Tensor, E: int) -> torch.Tensor:
+    _chk(expert_idxs, torch.int32)
+    _chk(gates, torch.float32)
+    _chk(dgates, torch.float32)
+    T, k = expert_idxs.shape
+    if gates.numel() != T * k or dgates.numel() != T * k:
+        raise ValueError("gates and dgates must hold T*k entries")
+    dlogits = torch.empty(T, E, dtype=torch.float32, device=gates.device)
+    _check(lib.smoe_topk_gate_bwd(ctx(), _stream(), _p(expert_idxs), _p(gates), _p(dgates), T, E, k, _p(dlogits)),
+           "smoe_topk_gate_bwd")
+    return dlogits
 
 
 def route(expert_idxs: torch.Tensor, E: int) -> Routing:

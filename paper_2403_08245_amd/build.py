@@ -1,4 +1,4 @@
-"""Builds libsmoe.so (HIP, gfx950) in-tree with hipcc.  Usage: python -m paper_2403_08245_amd.build"""
+"""Builds libsmoe.so (HIP, gfx950) in-tree with hipcc.  Usage: python paper_2403_08245_amd/build.py (or python __graft_entry__.py, which also imports the package)"""
 from __future__ import annotations
 
 import glob

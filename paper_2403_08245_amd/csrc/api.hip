@@ -92,6 +92,15 @@ int smoe_topk_gate(smoe_ctx *ctx, void *stream, const float *logits, int T, int 
   return launch_topk_gate((hipStream_t)stream, logits, T, E, k, expert_idxs, gates);
 }
 
+int smoe_topk_gate_bwd(smoe_ctx *ctx, void *stream, const int32_t *expert_idxs, const float *gates, const float *dgates,
+                       int T, int E, int k, float *dlogits) {
+  if (!ctx || T < 0 || E < 1 || k < 1 || k > E) return SMOE_ERR_INVALID_ARG;
+  if (T == 0) return SMOE_OK;
+  if (!expert_idxs || !gates || !dgates || !dlogits) return SMOE_ERR_INVALID_ARG;
+  if ((long long)T * k > 0x7fffffffLL) return SMOE_ERR_UNSUPPORTED;
+  return launch_topk_gate_bwd((hipStream_t)stream, expert_idxs, gates, dgates, T, E, k, dlogits);
+}
+
 size_t smoe_route_workspace_bytes(int T, int k, int E) {
   if (T < 0 || k < 1 || E < 1) return 0;
   return route_workspace_bytes(T * k, E);

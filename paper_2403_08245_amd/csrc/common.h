@@ -42,6 +42,8 @@ __device__ __forceinline__ int map_row(const RowMap &m, int i) {
 
 // ---- routing.hip
 int launch_topk_gate(hipStream_t s, const float *logits, int T, int E, int k, int32_t *idx, float *gates);
+int launch_topk_gate_bwd(hipStream_t s, const int32_t *idx, const float *gates, const float *dgates, int T, int E, int k,
+                         float *dlogits);
 size_t route_workspace_bytes(int Tk, int E);
 int launch_route(hipStream_t s, const int32_t *expert_idxs, int Tk, int E, int32_t *sorted_e,
                  int32_t *sorted_s, int32_t *offsets, void *ws);

@@ -83,6 +83,37 @@ int launch_topk_gate(hipStream_t s, const float *logits, int T, int E, int k, in
   return SMOE_OK;
 }
 
+// Gradient of the gate with respect to the router logits: softmax Jacobian on the k kept
+// experts (g_j (dp_j - sum_i g_i dp_i)), zero elsewhere.  One thread per (token, expert)
+// element so the [T,E] row is written whole and coalesced.
+__global__ void __launch_bounds__(256) topk_gate_bwd_kernel(const int32_t *__restrict__ idx,
+                                                            const float *__restrict__ gates,
+                                                            const float *__restrict__ dgates, size_t total, int E, int k,
+                                                            float *__restrict__ dlogits) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= total) return;
+  size_t t = i / E;
+  int e = (int)(i - t * E);
+  const size_t base = t * k;
+  float dot = 0.f, g_mine = 0.f, dp_mine = 0.f;
+  for (int j = 0; j < k; ++j) {
+    float g = gates[base + j], dp = dgates[base + j];
+    dot += g * dp;
+    if (idx[base + j] == e) { g_mine = g; dp_mine = dp; }
+  }
+  dlogits[i] = g_mine * (dp_mine - dot);
+}
+
+int launch_topk_gate_bwd(hipStream_t s, const int32_t *idx, const float *gates, const float *dgates, int T, int E, int k,
+                         float *dlogits) {
+  size_t total = (size_t)T * E;
+  if (total == 0) return SMOE_OK;
+  hipLaunchKernelGGL(topk_gate_bwd_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, idx, gates, dgates, total,
+                     E, k, dlogits);
+  SMOE_LAUNCH_CHECK();
+  return SMOE_OK;
+}
+
 // ---------------------------------------------------------------------------------------
 // Stable bucket sort by expert in three launches:
 //   1. each 64-lane block counts the experts of its contiguous chunk of slots,

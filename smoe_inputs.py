@@ -61,6 +61,13 @@ CONFIGS = {
     "C3-small": MLPConfig("C3-small", 1024, 256, 896, 8, 2, ACT_SWIGLU, zipf_s=1.2),
     "C3-small-f32": MLPConfig("C3-small-f32", 1024, 256, 896, 8, 2, ACT_SWIGLU, "f32", zipf_s=1.2),
 }
+# Unit-benchmark shapes of Sec. 4.1 / 4.2: d_model = 4096, d_ff = 2 d_model active hidden units,
+# d_expert = d_ff / k, E = 8k, T = 30 * 2048 tokens, granularity k in {1, 2, 4, 8, 16}; "G-dense" is
+# the dense MLP with the same active parameters (one expert of width d_ff that every token uses).
+GRANULARITY_KS = (1, 2, 4, 8, 16)
+for _k in GRANULARITY_KS:
+    CONFIGS[f"G{_k}"] = MLPConfig(f"G{_k}", 30 * 2048, 4096, 8192 // _k, 8 * _k, _k, ACT_GELU)
+CONFIGS["G-dense"] = MLPConfig("G-dense", 30 * 2048, 4096, 8192, 1, 1, ACT_GELU)
 
 # Mixture-of-Attention projections (Alg. 4): W_Q [E,d_model,d_out], W_O [E,d_out,d_model]
 MOA_C5 = dict(T=8192, d_model=2048, E=16, k=4, d_out=512)

@@ -157,6 +157,13 @@ def test_C4_granular_sampled(smoe):
     _run_fullsize(smoe, si.CONFIGS["C4"], 0, tokens_per_expert=1, dw_samples=1)
 
 
+@pytest.mark.parametrize("name", ["G4", "G16"])
+def test_unit_benchmark_shapes_sampled(smoe, name):
+    """Sec. 4.1 / 4.2 shapes (d_model 4096, d_expert = 8192/k, E = 8k, 61440 tokens): the headline k = 4 and the
+    finest granularity k = 16 (128 experts, 983040 routed rows)."""
+    _run_fullsize(smoe, si.CONFIGS[name], 0, tokens_per_expert=1, dw_samples=1)
+
+
 @pytest.mark.parametrize("name", ["C4-decode", "C4-decode-masked"])
 def test_C4_decode_forward_only(smoe, name):
     cfg = si.CONFIGS[name]

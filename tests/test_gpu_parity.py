@@ -48,6 +48,23 @@ def test_topk_and_route_bit_exact(smoe, T, E, k):
     assert np.array_equal(r.expert_offsets.cpu().numpy(), off)
 
 
+@pytest.mark.parametrize("T,E,k", [(1, 1, 1), (257, 8, 2), (1000, 64, 8), (333, 130, 16), (64, 5, 5)])
+def test_router_gradient(smoe, T, E, k):
+    """dlogits from Alg. 2's dp through the softmax over the kept logits (fp32 against the fp64 definition)."""
+    gen = torch.Generator().manual_seed(T + 7 * E + k)
+    logits = torch.randn(T, E, generator=gen, dtype=torch.float32)
+    dp = torch.randn(T, k, generator=gen, dtype=torch.float32)
+    gi, gg = smoe.topk_gate(logits.cuda(), k)
+    got = smoe.topk_gate_bwd(gi, gg, dp.cuda(), E).cpu().numpy().astype(np.float64)
+    ei, g = oracle.topk_gate(logits.numpy(), k)
+    ref = oracle.topk_gate_bwd(ei, g, dp.numpy().astype(np.float64), E)
+    assert got.shape == ref.shape
+    assert np.abs(got - ref).max() <= TOL[torch.float32] * max(np.abs(ref).max(), 1e-30)
+    mask = np.ones_like(ref, dtype=bool)
+    np.put_along_axis(mask, ei.astype(np.int64), False, axis=1)
+    assert (got[mask] == 0).all()                     # experts that were not kept get an exact zero
+
+
 def test_topk_ties_and_quantised_logits(smoe):
     g = torch.Generator().manual_seed(5)
     logits = torch.randint(-2, 3, (2048, 16), generator=g).to(torch.float32)     # many exact ties

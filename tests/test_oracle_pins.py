@@ -309,6 +309,50 @@ def test_topk_ties_go_to_lower_expert_id():
     np.testing.assert_allclose(g, 0.5)
 
 
+def test_router_gradient_hand_example_and_closed_forms():
+    # kept logits (ln 3, 0) give gates (3/4, 1/4); with dp = (1, 0) the softmax Jacobian gives
+    # dlogit = g0 (1 - g0) = 3/16 on the first kept expert and -g0 g1 = -3/16 on the second
+    logits = np.array([[-5.0, math.log(3.0), 0.0, -7.0]])
+    ei, g = oracle.topk_gate(logits, 2)
+    assert ei.tolist() == [[1, 2]]
+    dl = oracle.topk_gate_bwd(ei, g, np.array([[1.0, 0.0]]), 4)
+    np.testing.assert_allclose(dl, [[0.0, 3 / 16, -3 / 16, 0.0]], atol=1e-15)
+    # k = 1: the only gate is the constant 1, no gradient reaches the router
+    r = RNG(0)
+    lg = r.standard_normal((6, 5))
+    ei, g = oracle.topk_gate(lg, 1)
+    assert np.abs(oracle.topk_gate_bwd(ei, g, r.standard_normal((6, 1)), 5)).max() == 0
+    # softmax is shift invariant: every row of the gradient sums to zero; experts not kept get zero
+    ei, g = oracle.topk_gate(lg, 3)
+    dl = oracle.topk_gate_bwd(ei, g, r.standard_normal((6, 3)), 5)
+    np.testing.assert_allclose(dl.sum(axis=1), 0, atol=1e-15)
+    mask = np.ones_like(dl, dtype=bool)
+    np.put_along_axis(mask, ei.astype(np.int64), False, axis=1)
+    assert np.abs(dl[mask]).max() == 0 and np.abs(dl[~mask]).min() > 0
+
+
+def test_router_gradient_vs_finite_differences():
+    r = RNG(3)
+    T, E, k = 5, 6, 3
+    lg = r.permuted(np.tile(np.arange(E, dtype=np.float64), (T, 1)), axis=1) * 0.7 + r.uniform(-0.1, 0.1, (T, E))
+    dp = r.standard_normal((T, k))
+    ei, g = oracle.topk_gate(lg, k)
+    dl = oracle.topk_gate_bwd(ei, g, dp, E)
+
+    def loss(l):
+        ei2, g2 = oracle.topk_gate(l, k)
+        assert np.array_equal(ei2, ei)          # logits are 0.5 apart at least: the selection does not move
+        return float((g2 * dp).sum())
+
+    h = 1e-6
+    for t in range(T):
+        for e in range(E):
+            lp, lm = lg.copy(), lg.copy()
+            lp[t, e] += h
+            lm[t, e] -= h
+            assert abs((loss(lp) - loss(lm)) / (2 * h) - dl[t, e]) < 1e-8
+
+
 def test_route_with_empty_experts_and_single_expert():
     se, o, off = oracle.route(np.array([[3, 3], [3, 3]]), 5)
     assert off.tolist() == [0, 0, 0, 0, 4, 4] and o.tolist() == [0, 1, 2, 3]
