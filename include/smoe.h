@@ -174,6 +174,17 @@ int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
 int smoe_group(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *in, int d,
                const smoe_routing *r, int fan, const float *gates, void *out);
 
+/* ---- SMoE multi-head attention: Alg. 4, Sec. 3.3 ------------------------------------------
+ * The attention between Alg. 4's two scattered->scattered ParallelLinears: causal scaled
+ * dot-product attention softmax(q k^T / sqrt(d_head)) v inside each of the B sequences of T
+ * positions, grouped-query style: Q and O hold one row per routed slot, [B, T, G, h, d_head]
+ * (G = k slots per token, h = heads per expert), K and V one row per token, [B, T, h, d_head];
+ * head hh of every slot attends key/value head hh (Sec. 3.3).
+ *   LSE [B, T, G, h] fp32 (out): log-sum-exp of the scaled, masked scores, kept for the backward.
+ * bf16 only, d_head = 128 (else SMOE_ERR_UNSUPPORTED).  No workspace. */
+int smoe_attention_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *Q, const void *K,
+                       const void *V, int B, int T, int G, int h, int d_head, void *O, float *LSE);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ EXPORTS = [
     "smoe_topk_gate", "smoe_topk_gate_bwd", "smoe_route_workspace_bytes", "smoe_route",
     "smoe_plinear_fwd", "smoe_plinear_bwd_workspace_bytes", "smoe_plinear_bwd",
     "smoe_mlp_fwd_workspace_bytes", "smoe_mlp_fwd", "smoe_mlp_bwd_workspace_bytes", "smoe_mlp_bwd",
-    "smoe_group",
+    "smoe_group", "smoe_attention_fwd",
 ]
 
 
@@ -55,6 +55,7 @@ lib.smoe_strerror.restype = ctypes.c_char_p
 lib.smoe_set_kernel_mode.argtypes = [_vp, _i]
 lib.smoe_topk_gate.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp, _vp]
 lib.smoe_topk_gate_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp]
+lib.smoe_attention_fwd.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp]
 lib.smoe_route_workspace_bytes.argtypes = [_i, _i, _i]
 lib.smoe_route_workspace_bytes.restype = _sz
 lib.smoe_route.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _sz]
@@ -161,6 +162,20 @@ def topk_gate_bwd(expert_idxs: torch.Tensor, gates: torch.Tensor, dgates: torch.
     _check(lib.smoe_topk_gate_bwd(ctx(), _stream(), _p(expert_idxs), _p(gates), _p(dgates), T, E, k, _p(dlogits)),
            "smoe_topk_gate_bwd")
     return dlogits
+
+
+def attention_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor):
+    """Q [B,T,G,h,d], K and V [B,T,h,d] (bf16) -> O like Q, LSE [B,T,G,h] fp32."""
+    for t in (Q, K, V):
+        _chk(t, torch.bfloat16)
+    B, T, G, h, d = Q.shape
+    if K.shape != (B, T, h, d) or V.shape != K.shape:
+        raise ValueError("K and V must be [B, T, h, d]")
+    O = torch.empty_like(Q)
+    LSE = torch.empty(B, T, G, h, dtype=torch.float32, device=Q.device)
+    _check(lib.smoe_attention_fwd(ctx(), _stream(), BF16, _p(Q), _p(K), _p(V), B, T, G, h, d, _p(O), _p(LSE)),
+           "smoe_attention_fwd")
+    return O, LSE
 
 
 def route(expert_idxs: torch.Tensor, E: int) -> Routing:

@@ -101,6 +101,22 @@ int smoe_topk_gate_bwd(smoe_ctx *ctx, void *stream, const int32_t *expert_idxs, 
   return launch_topk_gate_bwd((hipStream_t)stream, expert_idxs, gates, dgates, T, E, k, dlogits);
 }
 
+static int attention_args_ok(smoe_dtype dtype, int B, int T, int G, int h, int d_head) {
+  if (B < 1 || T < 1 || G < 1 || h < 1 || d_head < 1) return SMOE_ERR_INVALID_ARG;
+  if (dtype != SMOE_BF16 || d_head != 128) return SMOE_ERR_UNSUPPORTED;
+  if ((long long)T * G > 0x3fffffffLL || (long long)B * T * G > 0x7fffffffLL || h > 65535 || B > 65535)
+    return SMOE_ERR_UNSUPPORTED;
+  return SMOE_OK;
+}
+
+int smoe_attention_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *Q, const void *K, const void *V, int B,
+                       int T, int G, int h, int d_head, void *O, float *LSE) {
+  if (!ctx || !Q || !K || !V || !O || !LSE) return SMOE_ERR_INVALID_ARG;
+  int rc = attention_args_ok(dtype, B, T, G, h, d_head);
+  if (rc != SMOE_OK) return rc;
+  return launch_attn_fwd((hipStream_t)stream, Q, K, V, O, LSE, B, T, G, h);
+}
+
 size_t smoe_route_workspace_bytes(int T, int k, int E) {
   if (T < 0 || k < 1 || E < 1) return 0;
   return route_workspace_bytes(T * k, E);

@@ -1,0 +1,195 @@
+// Causal grouped-query attention for the SMoE attention layer (Alg. 4, Sec. 3.3), bf16 in and
+// out, fp32 softmax statistics and accumulation on the matrix cores.
+//
+// Q and O hold one row per routed slot, [B, T, G, h, 128] (G = the k slots of a token, h heads
+// per expert); K and V hold one row per token, [B, T, h, 128].  Head hh of every slot attends
+// key/value head hh of the positions <= its own inside its sequence.
+//
+// All three kernels work on transposed score tiles S^T[key][query] = K Q^T so that a lane of
+// the 32x32 matrix instruction owns ONE query column: its softmax statistics are per-lane
+// scalars, and the probabilities leave the accumulator registers already in the layout the
+// next product takes as its B operand (no cross-lane shuffles; the matching operand is read
+// from LDS in the same permuted key order).
+#include "mfma_common.h"
+
+namespace {
+
+constexpr int AD = 128;             // head width
+constexpr int AKT = 32;             // keys (or query rows) per LDS tile
+constexpr int AROW = AD * 2;        // bytes per tile row
+constexpr int ATILE = AKT * AROW;   // 8 KB
+constexpr int AQ = 128;             // rows per block: 32 per wavefront
+constexpr float NEG_BIG = -1.0e30f; // finite stand-in for -inf: exp2 of it is 0 and no inf - inf appears
+
+// 16-byte chunk swizzle of a 256-byte row: conflict free both for the row-per-lane reads
+// (16 consecutive rows -> 16 positions) and for the transposing reads (4 consecutive rows ->
+// 4 different 64-byte segments).
+__device__ __forceinline__ int a_swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
+
+// One wavefront's share (2 of 8 instructions) of loading a [32 x 128] tile whose row r comes
+// from `base + row_index(r) * ld`; rows past `last` repeat row `last`.
+__device__ __forceinline__ void load_tile_rows(const bf16_t *base, size_t ld, int row0, int last, uint32_t lds_tile,
+                                               int wave, int uwave, int lane) {
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    int i = wave * 2 + u;
+    int row = 4 * i + (lane >> 4);
+    int chunk = (lane & 15) ^ a_swz(row);
+    int src = min(row0 + row, last);
+    load16_to_lds(base + (size_t)src * ld + chunk * 8, lds_tile + (uwave * 2 + u) * 1024);
+  }
+}
+
+// A operand, tile rows as matrix rows: lane -> row (lane % 32), columns 16*ks + 8*(lane/32) + 0..7
+__device__ __forceinline__ bf16x8 a_rows_frag(const char *tile, int ks, int lane) {
+  int row = lane & 31;
+  int chunk = (2 * ks + (lane >> 5)) ^ a_swz(row);
+  return *reinterpret_cast<const bf16x8 *>(tile + row * AROW + (chunk << 4));
+}
+// A operand, tile columns as matrix rows (the tile transposed): lane -> column c0 + lane % 32 and
+// the eight tile rows 16*s + 4*(lane/32) + {0..3, 8..11}: the order in which a lane's accumulator
+// registers of a [tile row][x] product enumerate the tile rows, so those registers can be the B
+// operand of the next product as they are.
+__device__ __forceinline__ bf16x8 a_cols_frag(const char *tile, int c0, int s, int lane) {
+  int col = c0 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  int row0 = 16 * s + 4 * (lane >> 5) + ((lane & 15) >> 2);
+  union { bf16x8 v; s16x4 h[2]; } u;
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    int row = row0 + 8 * t;
+    int off = row * AROW + (((col >> 3) ^ a_swz(row)) << 4) + ((col & 7) << 1);
+    u.h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4 *)(tile + off));
+  }
+  return u.v;
+}
+// tile row that accumulator register q of this lane belongs to (32x32 result layout)
+__device__ __forceinline__ int acc_row(int q, int lane) { return 8 * (q >> 2) + 4 * (lane >> 5) + (q & 3); }
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16 &p, int s) {
+  bf16x8 v;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) v[c] = (bf16_t)p[8 * s + c];
+  return v;
+}
+
+struct AttnDims {
+  int B, T, G, h;
+  size_t ldq, ldkv;    // row strides in elements: h * 128
+  float scale_log2;    // log2(e) / sqrt(128)
+};
+
+// ======================================================================================
+// forward: block = (query tile of 128 slot rows, head, sequence); keys stream through LDS
+// ======================================================================================
+__global__ void __launch_bounds__(256) attn_fwd_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                                       const bf16_t *__restrict__ V, bf16_t *__restrict__ O,
+                                                       float *__restrict__ LSE, AttnDims d) {
+  __shared__ __attribute__((aligned(1024))) char smem[4 * ATILE];   // two stages of (K tile, V tile)
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int uwave = __builtin_amdgcn_readfirstlane(wave);
+  const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;              // long rows first
+  const int hh = blockIdx.y, b = blockIdx.z;
+  const int rows = d.T * d.G;                                        // slot rows of one sequence
+  const int R0 = qt * AQ;
+  const int r_mine = min(R0 + wave * 32 + (lane & 31), rows - 1);
+  const int tok = r_mine / d.G;
+  const int wave_first = min(R0 + wave * 32, rows - 1) / d.G;
+  const int wave_last = min(R0 + wave * 32 + 31, rows - 1) / d.G;
+  const int n_tiles = min(R0 + AQ - 1, rows - 1) / d.G / AKT + 1;
+  const bool row_valid = R0 + wave * 32 + (lane & 31) < rows;
+
+  const bf16_t *Kb = K + (size_t)b * d.T * d.ldkv + hh * AD;
+  const bf16_t *Vb = V + (size_t)b * d.T * d.ldkv + hh * AD;
+  const size_t qrow = ((size_t)b * rows + r_mine) * d.ldq + hh * AD;
+  bf16x8 qf[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(Q + qrow + 16 * ks + 8 * (lane >> 5));
+
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
+  f32x16 acc[4];
+#pragma unroll
+  for (int f = 0; f < 4; ++f)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc[f][q] = 0.f;
+  float m = NEG_BIG, l = 0.f;
+
+  load_tile_rows(Kb, d.ldkv, 0, d.T - 1, lds0, wave, uwave, lane);
+  load_tile_rows(Vb, d.ldkv, 0, d.T - 1, lds0 + ATILE, wave, uwave, lane);
+  for (int j = 0; j < n_tiles; ++j) {
+    wait_loads<0>();
+    __syncthreads();   // tile j has landed for everyone; everyone is done reading tile j-1
+    if (j + 1 < n_tiles) {
+      uint32_t nxt = lds0 + ((j + 1) & 1) * 2 * ATILE;
+      load_tile_rows(Kb, d.ldkv, (j + 1) * AKT, d.T - 1, nxt, wave, uwave, lane);
+      load_tile_rows(Vb, d.ldkv, (j + 1) * AKT, d.T - 1, nxt + ATILE, wave, uwave, lane);
+    }
+    const int key0 = j * AKT;
+    if (key0 > wave_last) continue;   // wave-uniform: every key of the tile is in the future of all 32 rows
+    const char *kt = smem + (j & 1) * 2 * ATILE;
+    const char *vt = kt + ATILE;
+    f32x16 s;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) s[q] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_rows_frag(kt, ks, lane), qf[ks], s, 0, 0, 0);
+    const bool diag = key0 + AKT - 1 > wave_first;
+    float mx = NEG_BIG;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      float v = s[q] * d.scale_log2;
+      if (diag && key0 + acc_row(q, lane) > tok) v = NEG_BIG;
+      s[q] = v;
+      mx = fmaxf(mx, v);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m, mx);
+    const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+    float psum = 0.f;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      float p = __builtin_amdgcn_exp2f(s[q] - m_new);
+      s[q] = p;
+      psum += p;
+    }
+    l = l * alpha + psum;
+    m = m_new;
+#pragma unroll
+    for (int f = 0; f < 4; ++f)
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc[f][q] *= alpha;
+    bf16x8 pb[2] = {pack8(s, 0), pack8(s, 1)};
+#pragma unroll
+    for (int f = 0; f < 4; ++f)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
+        acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cols_frag(vt, f * 32, s2, lane), pb[s2], acc[f], 0, 0, 0);
+  }
+  // the two halves of the wavefront hold disjoint key subsets of the same query
+  const float l_tot = l + __shfl_xor(l, 32, 64);
+  const float inv = 1.0f / l_tot;
+  if (row_valid) {
+    bf16_t *orow = O + qrow;
+#pragma unroll
+    for (int f = 0; f < 4; ++f)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 v;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v[c] = (bf16_t)(acc[f][4 * g + c] * inv);
+        *reinterpret_cast<bf16x4 *>(orow + f * 32 + 8 * g + 4 * (lane >> 5)) = v;
+      }
+    if (lane < 32) LSE[((size_t)b * rows + r_mine) * d.h + hh] = (m + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+  }
+}
+
+}  // namespace
+
+int launch_attn_fwd(hipStream_t s, const void *Q, const void *K, const void *V, void *O, float *LSE, int B, int T, int G,
+                    int h) {
+  AttnDims d{B, T, G, h, (size_t)h * AD, (size_t)h * AD, 1.4426950408889634f / sqrtf((float)AD)};
+  int q_tiles = ceil_div(T * G, AQ);
+  hipLaunchKernelGGL(attn_fwd_kernel, dim3(q_tiles, h, B), dim3(256), 0, s, (const bf16_t *)Q, (const bf16_t *)K,
+                     (const bf16_t *)V, (bf16_t *)O, LSE, d);
+  SMOE_LAUNCH_CHECK();
+  return SMOE_OK;
+}
