@@ -24,7 +24,7 @@ EXPORTS = [
     "smoe_topk_gate", "smoe_topk_gate_bwd", "smoe_route_workspace_bytes", "smoe_route",
     "smoe_plinear_fwd", "smoe_plinear_bwd_workspace_bytes", "smoe_plinear_bwd",
     "smoe_mlp_fwd_workspace_bytes", "smoe_mlp_fwd", "smoe_mlp_bwd_workspace_bytes", "smoe_mlp_bwd",
-    "smoe_group", "smoe_attention_fwd",
+    "smoe_group", "smoe_attention_fwd", "smoe_attention_bwd_workspace_bytes", "smoe_attention_bwd",
 ]
 
 
@@ -56,6 +56,9 @@ lib.smoe_set_kernel_mode.argtypes = [_vp, _i]
 lib.smoe_topk_gate.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp, _vp]
 lib.smoe_topk_gate_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp]
 lib.smoe_attention_fwd.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp]
+lib.smoe_attention_bwd_workspace_bytes.argtypes = [_i, _i, _i, _i]
+lib.smoe_attention_bwd_workspace_bytes.restype = _sz
+lib.smoe_attention_bwd.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz]
 lib.smoe_route_workspace_bytes.argtypes = [_i, _i, _i]
 lib.smoe_route_workspace_bytes.restype = _sz
 lib.smoe_route.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _sz]
@@ -176,6 +179,19 @@ def attention_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor):
     _check(lib.smoe_attention_fwd(ctx(), _stream(), BF16, _p(Q), _p(K), _p(V), B, T, G, h, d, _p(O), _p(LSE)),
            "smoe_attention_fwd")
     return O, LSE
+
+
+def attention_bwd(dO, Q, K, V, O, LSE):
+    for t in (dO, Q, K, V, O):
+        _chk(t, torch.bfloat16)
+    _chk(LSE, torch.float32)
+    B, T, G, h, d = Q.shape
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    nb = lib.smoe_attention_bwd_workspace_bytes(B, T, G, h)
+    ws = _ws(nb, Q.device)
+    _check(lib.smoe_attention_bwd(ctx(), _stream(), BF16, _p(dO), _p(Q), _p(K), _p(V), _p(O), _p(LSE), B, T, G, h, d,
+                                  _p(dQ), _p(dK), _p(dV), _p(ws), nb), "smoe_attention_bwd")
+    return dQ, dK, dV
 
 
 def route(expert_idxs: torch.Tensor, E: int) -> Routing:

@@ -117,6 +117,21 @@ int smoe_attention_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void
   return launch_attn_fwd((hipStream_t)stream, Q, K, V, O, LSE, B, T, G, h);
 }
 
+size_t smoe_attention_bwd_workspace_bytes(int B, int T, int G, int h) {
+  if (B < 1 || T < 1 || G < 1 || h < 1) return 0;
+  return align256((size_t)B * T * G * h * sizeof(float));
+}
+
+int smoe_attention_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *dO, const void *Q, const void *K,
+                       const void *V, const void *O, const float *LSE, int B, int T, int G, int h, int d_head, void *dQ,
+                       void *dK, void *dV, void *ws, size_t ws_bytes) {
+  if (!ctx || !dO || !Q || !K || !V || !O || !LSE || !dQ || !dK || !dV) return SMOE_ERR_INVALID_ARG;
+  int rc = attention_args_ok(dtype, B, T, G, h, d_head);
+  if (rc != SMOE_OK) return rc;
+  if (!ws || ((uintptr_t)ws & 255) || ws_bytes < smoe_attention_bwd_workspace_bytes(B, T, G, h)) return SMOE_ERR_WORKSPACE;
+  return launch_attn_bwd((hipStream_t)stream, Q, K, V, O, dO, LSE, (float *)ws, dQ, dK, dV, B, T, G, h);
+}
+
 size_t smoe_route_workspace_bytes(int T, int k, int E) {
   if (T < 0 || k < 1 || E < 1) return 0;
   return route_workspace_bytes(T * k, E);

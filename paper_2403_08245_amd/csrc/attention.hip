@@ -182,6 +182,236 @@ __global__ void __launch_bounds__(256) attn_fwd_kernel(const bf16_t *__restrict_
   }
 }
 
+
+// ======================================================================================
+// backward, part 0: delta[row][head] = <dO, O> over the head's 128 columns (one wavefront each)
+// ======================================================================================
+__global__ void __launch_bounds__(256) attn_delta_kernel(const bf16_t *__restrict__ O, const bf16_t *__restrict__ dO,
+                                                         float *__restrict__ delta, size_t n) {
+  size_t i = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // (row, head) pair; both tensors are [rows][h][128]
+  if (i >= n) return;
+  const int lane = threadIdx.x & 63;
+  const bf16_t *a = O + i * AD + lane * 2, *b = dO + i * AD + lane * 2;
+  float v = (float)a[0] * (float)b[0] + (float)a[1] * (float)b[1];
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d, 64);
+  if (lane == 0) delta[i] = v;
+}
+
+// ======================================================================================
+// backward, part 1: dQ.  Same walk as the forward; a lane owns one query row.
+//   S^T = K Q^T, P^T = exp2(S^T * c - lse), dP^T = V dO^T, dS^T = P^T (dP^T - delta) / sqrt(d),
+//   dQ^T += K^T dS^T
+// ======================================================================================
+__global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                                          const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
+                                                          const float *__restrict__ LSE, const float *__restrict__ delta,
+                                                          bf16_t *__restrict__ dQ, AttnDims d) {
+  __shared__ __attribute__((aligned(1024))) char smem[4 * ATILE];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int uwave = __builtin_amdgcn_readfirstlane(wave);
+  const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;
+  const int hh = blockIdx.y, b = blockIdx.z;
+  const int rows = d.T * d.G;
+  const int R0 = qt * AQ;
+  const int r_mine = min(R0 + wave * 32 + (lane & 31), rows - 1);
+  const int tok = r_mine / d.G;
+  const int wave_first = min(R0 + wave * 32, rows - 1) / d.G;
+  const int wave_last = min(R0 + wave * 32 + 31, rows - 1) / d.G;
+  const int n_tiles = min(R0 + AQ - 1, rows - 1) / d.G / AKT + 1;
+  const bool row_valid = R0 + wave * 32 + (lane & 31) < rows;
+
+  const bf16_t *Kb = K + (size_t)b * d.T * d.ldkv + hh * AD;
+  const bf16_t *Vb = V + (size_t)b * d.T * d.ldkv + hh * AD;
+  const size_t qrow = ((size_t)b * rows + r_mine) * d.ldq + hh * AD;
+  bf16x8 qf[8], dof[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    qf[ks] = *reinterpret_cast<const bf16x8 *>(Q + qrow + 16 * ks + 8 * (lane >> 5));
+    dof[ks] = *reinterpret_cast<const bf16x8 *>(dO + qrow + 16 * ks + 8 * (lane >> 5));
+  }
+  const size_t stat = ((size_t)b * rows + r_mine) * d.h + hh;
+  const float lse2 = LSE[stat] * 1.4426950408889634f;
+  const float dlt = delta[stat];
+  const float scale = d.scale_log2 * 0.6931471805599453f;
+
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
+  f32x16 acc[4];
+#pragma unroll
+  for (int f = 0; f < 4; ++f)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc[f][q] = 0.f;
+
+  load_tile_rows(Kb, d.ldkv, 0, d.T - 1, lds0, wave, uwave, lane);
+  load_tile_rows(Vb, d.ldkv, 0, d.T - 1, lds0 + ATILE, wave, uwave, lane);
+  for (int j = 0; j < n_tiles; ++j) {
+    wait_loads<0>();
+    __syncthreads();
+    if (j + 1 < n_tiles) {
+      uint32_t nxt = lds0 + ((j + 1) & 1) * 2 * ATILE;
+      load_tile_rows(Kb, d.ldkv, (j + 1) * AKT, d.T - 1, nxt, wave, uwave, lane);
+      load_tile_rows(Vb, d.ldkv, (j + 1) * AKT, d.T - 1, nxt + ATILE, wave, uwave, lane);
+    }
+    const int key0 = j * AKT;
+    if (key0 > wave_last) continue;
+    const char *kt = smem + (j & 1) * 2 * ATILE;
+    const char *vt = kt + ATILE;
+    f32x16 s, dp;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) { s[q] = 0.f; dp[q] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_rows_frag(kt, ks, lane), qf[ks], s, 0, 0, 0);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_rows_frag(vt, ks, lane), dof[ks], dp, 0, 0, 0);
+    const bool diag = key0 + AKT - 1 > wave_first;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      float p = __builtin_amdgcn_exp2f(s[q] * d.scale_log2 - lse2);
+      if (diag && key0 + acc_row(q, lane) > tok) p = 0.f;
+      s[q] = p * (dp[q] - dlt) * scale;
+    }
+    bf16x8 db[2] = {pack8(s, 0), pack8(s, 1)};
+#pragma unroll
+    for (int f = 0; f < 4; ++f)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
+        acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cols_frag(kt, f * 32, s2, lane), db[s2], acc[f], 0, 0, 0);
+  }
+  if (row_valid) {
+    bf16_t *orow = dQ + qrow;
+#pragma unroll
+    for (int f = 0; f < 4; ++f)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 v;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) v[c] = (bf16_t)acc[f][4 * g + c];
+        *reinterpret_cast<bf16x4 *>(orow + f * 32 + 8 * g + 4 * (lane >> 5)) = v;
+      }
+  }
+}
+
+// ======================================================================================
+// backward, part 2: dK and dV.  Block = 128 keys of one (sequence, head), 32 per wavefront, a
+// lane owns one key; the slot rows that can see them stream through LDS 32 at a time.
+//   S = Q K^T, P = exp2(S c - lse[row]), dV^T += dO^T P, dP = dO V^T,
+//   dS = P (dP - delta[row]) / sqrt(d), dK^T += Q^T dS
+// ======================================================================================
+__global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                                           const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
+                                                           const float *__restrict__ LSE, const float *__restrict__ delta,
+                                                           bf16_t *__restrict__ dK, bf16_t *__restrict__ dV, AttnDims d) {
+  __shared__ __attribute__((aligned(1024))) char smem[4 * ATILE];
+  __shared__ __attribute__((aligned(16))) float s_lse[2][AKT], s_dlt[2][AKT];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int uwave = __builtin_amdgcn_readfirstlane(wave);
+  const int kb = blockIdx.x;                                   // early keys have the long row lists
+  const int hh = blockIdx.y, b = blockIdx.z;
+  const int rows = d.T * d.G;
+  const int k0 = kb * AQ;
+  const int key = min(k0 + wave * 32 + (lane & 31), d.T - 1);
+  const bool key_valid = k0 + wave * 32 + (lane & 31) < d.T;
+  const int wave_key0 = k0 + wave * 32;
+
+  const size_t krow = ((size_t)b * d.T + key) * d.ldkv + hh * AD;
+  bf16x8 kf[8], vf[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    kf[ks] = *reinterpret_cast<const bf16x8 *>(K + krow + 16 * ks + 8 * (lane >> 5));
+    vf[ks] = *reinterpret_cast<const bf16x8 *>(V + krow + 16 * ks + 8 * (lane >> 5));
+  }
+  const bf16_t *Qb = Q + (size_t)b * rows * d.ldq + hh * AD;
+  const bf16_t *dOb = dO + (size_t)b * rows * d.ldq + hh * AD;
+  const float *Lb = LSE + (size_t)b * rows * d.h + hh;
+  const float *Db = delta + (size_t)b * rows * d.h + hh;
+  const float scale = d.scale_log2 * 0.6931471805599453f;
+
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
+  f32x16 acck[4], accv[4];
+#pragma unroll
+  for (int f = 0; f < 4; ++f)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) { acck[f][q] = 0.f; accv[f][q] = 0.f; }
+
+  const int t_first = (k0 * d.G) / AKT;                        // first 32-row tile holding a row that sees key k0
+  const int n_tiles = (rows + AKT - 1) / AKT - t_first;
+  auto load_stats = [&](int tile, int stage) {
+    if (threadIdx.x < AKT) {
+      int r = min(tile * AKT + (int)threadIdx.x, rows - 1);
+      s_lse[stage][threadIdx.x] = Lb[(size_t)r * d.h] * 1.4426950408889634f;
+      s_dlt[stage][threadIdx.x] = Db[(size_t)r * d.h];
+    }
+  };
+  load_tile_rows(Qb, d.ldq, t_first * AKT, rows - 1, lds0, wave, uwave, lane);
+  load_tile_rows(dOb, d.ldq, t_first * AKT, rows - 1, lds0 + ATILE, wave, uwave, lane);
+  load_stats(t_first, 0);
+  for (int j = 0; j < n_tiles; ++j) {
+    wait_loads<0>();
+    __syncthreads();
+    const int tile = t_first + j;
+    if (j + 1 < n_tiles) {
+      uint32_t nxt = lds0 + ((j + 1) & 1) * 2 * ATILE;
+      load_tile_rows(Qb, d.ldq, (tile + 1) * AKT, rows - 1, nxt, wave, uwave, lane);
+      load_tile_rows(dOb, d.ldq, (tile + 1) * AKT, rows - 1, nxt + ATILE, wave, uwave, lane);
+      load_stats(tile + 1, (j + 1) & 1);
+    }
+    const int r0 = tile * AKT;
+    const int tile_last_tok = min(r0 + AKT - 1, rows - 1) / d.G;
+    if (tile_last_tok < wave_key0) continue;                    // none of these rows sees any key of this wavefront
+    const char *qt = smem + (j & 1) * 2 * ATILE;
+    const char *dot = qt + ATILE;
+    f32x16 s, dp;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) { s[q] = 0.f; dp[q] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_rows_frag(qt, ks, lane), kf[ks], s, 0, 0, 0);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_rows_frag(dot, ks, lane), vf[ks], dp, 0, 0, 0);
+    // rows of this tile that are earlier than the wavefront's last key, or past the end, need the mask
+    const bool edge = (r0 / d.G < wave_key0 + 31) || (r0 + AKT > rows);
+    f32x16 p;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int rr = 8 * g + 4 * (lane >> 5);
+      const float4 l4 = *reinterpret_cast<const float4 *>(&s_lse[j & 1][rr]);
+      const float4 d4 = *reinterpret_cast<const float4 *>(&s_dlt[j & 1][rr]);
+      const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int q = 4 * g + c;
+        float pv = __builtin_amdgcn_exp2f(s[q] * d.scale_log2 - lv[c]);
+        if (edge) {
+          int r = r0 + rr + c;
+          if (r >= rows || r / d.G < key) pv = 0.f;
+        }
+        p[q] = pv;
+        s[q] = pv * (dp[q] - dv[c]) * scale;
+      }
+    }
+    bf16x8 pb[2] = {pack8(p, 0), pack8(p, 1)};
+    bf16x8 db[2] = {pack8(s, 0), pack8(s, 1)};
+#pragma unroll
+    for (int f = 0; f < 4; ++f)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        accv[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cols_frag(dot, f * 32, s2, lane), pb[s2], accv[f], 0, 0, 0);
+        acck[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cols_frag(qt, f * 32, s2, lane), db[s2], acck[f], 0, 0, 0);
+      }
+  }
+  if (key_valid) {
+#pragma unroll
+    for (int f = 0; f < 4; ++f)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 vk, vv;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { vk[c] = (bf16_t)acck[f][4 * g + c]; vv[c] = (bf16_t)accv[f][4 * g + c]; }
+        *reinterpret_cast<bf16x4 *>(dK + krow + f * 32 + 8 * g + 4 * (lane >> 5)) = vk;
+        *reinterpret_cast<bf16x4 *>(dV + krow + f * 32 + 8 * g + 4 * (lane >> 5)) = vv;
+      }
+  }
+}
+
 }  // namespace
 
 int launch_attn_fwd(hipStream_t s, const void *Q, const void *K, const void *V, void *O, float *LSE, int B, int T, int G,
@@ -190,6 +420,22 @@ int launch_attn_fwd(hipStream_t s, const void *Q, const void *K, const void *V, 
   int q_tiles = ceil_div(T * G, AQ);
   hipLaunchKernelGGL(attn_fwd_kernel, dim3(q_tiles, h, B), dim3(256), 0, s, (const bf16_t *)Q, (const bf16_t *)K,
                      (const bf16_t *)V, (bf16_t *)O, LSE, d);
+  SMOE_LAUNCH_CHECK();
+  return SMOE_OK;
+}
+
+int launch_attn_bwd(hipStream_t s, const void *Q, const void *K, const void *V, const void *O, const void *dO,
+                    const float *LSE, float *delta, void *dQ, void *dK, void *dV, int B, int T, int G, int h) {
+  AttnDims d{B, T, G, h, (size_t)h * AD, (size_t)h * AD, 1.4426950408889634f / sqrtf((float)AD)};
+  size_t n = (size_t)B * T * G * h;
+  hipLaunchKernelGGL(attn_delta_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, s, (const bf16_t *)O, (const bf16_t *)dO,
+                     delta, n);
+  SMOE_LAUNCH_CHECK();
+  hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(ceil_div(T * G, AQ), h, B), dim3(256), 0, s, (const bf16_t *)Q,
+                     (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)dO, LSE, (const float *)delta, (bf16_t *)dQ, d);
+  SMOE_LAUNCH_CHECK();
+  hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3(ceil_div(T, AQ), h, B), dim3(256), 0, s, (const bf16_t *)Q, (const bf16_t *)K,
+                     (const bf16_t *)V, (const bf16_t *)dO, LSE, (const float *)delta, (bf16_t *)dK, (bf16_t *)dV, d);
   SMOE_LAUNCH_CHECK();
   return SMOE_OK;
 }

@@ -44,6 +44,8 @@ __device__ __forceinline__ int map_row(const RowMap &m, int i) {
 int launch_topk_gate(hipStream_t s, const float *logits, int T, int E, int k, int32_t *idx, float *gates);
 int launch_attn_fwd(hipStream_t s, const void *Q, const void *K, const void *V, void *O, float *LSE, int B, int T, int G,
                     int h);
+int launch_attn_bwd(hipStream_t s, const void *Q, const void *K, const void *V, const void *O, const void *dO,
+                    const float *LSE, float *delta, void *dQ, void *dK, void *dV, int B, int T, int G, int h);
 int launch_topk_gate_bwd(hipStream_t s, const int32_t *idx, const float *gates, const float *dgates, int T, int E, int k,
                          float *dlogits);
 size_t route_workspace_bytes(int Tk, int E);
