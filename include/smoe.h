@@ -195,6 +195,35 @@ int smoe_attention_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void
                        const void *K, const void *V, const void *O, const float *LSE, int B, int T, int G,
                        int h, int d_head, void *dQ, void *dK, void *dV, void *ws, size_t ws_bytes);
 
+/* SMoE multi-head attention layer, Alg. 4:
+ *   V = X W_V, K = X W_K (dense), Q = ParallelLinear(X, W_Q, o, no p, scattered -> scattered),
+ *   Ohat = Attention(Q, K, V), O = ParallelLinear(Ohat, W_O, o, p, scattered -> scattered).
+ *   X [B*T, d_model] (B sequences of T positions, batch-time order);  d_out = h_expert * d_head;
+ *   W_K, W_V [d_model, d_out];  W_Q [E, d_model, d_out];  W_O [E, d_out, d_model];
+ *   r, k, gates: routing of the B*T tokens (Tk = B*T*k);  O [B*T, d_model] (out).
+ *   saved_K, saved_V [B*T, d_out], saved_Q, saved_Ohat [Tk, d_out] (slot order), saved_LSE
+ *   [Tk, h_expert] fp32, saved_Yhat [Tk, d_model] (slot order): kept for the backward pass; pass
+ *   all six or none (inference: the workspace holds them).
+ * bf16, d_head = 128.  The dense projections run through the grouped kernels as one expert. */
+size_t smoe_momha_fwd_workspace_bytes(int B, int T, int k, int d_model, int h_expert, int d_head,
+                                      int training);
+int smoe_momha_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *X, int B, int T, int d_model,
+                   int h_expert, int d_head, const void *W_K, const void *W_V, const void *W_Q,
+                   const void *W_O, const smoe_routing *r, int k, const float *gates, void *O,
+                   void *saved_K, void *saved_V, void *saved_Q, void *saved_Ohat, float *saved_LSE,
+                   void *saved_Yhat, void *ws, size_t ws_bytes);
+
+/* Backward of smoe_momha_fwd: Alg. 2 for the two ParallelLinears, smoe_attention_bwd between
+ * them, plain products for the dense key/value projections.
+ *   dO [B*T, d_model] upstream gradient; dX like X; dW_* like W_*; dgates [Tk] fp32 (all out). */
+size_t smoe_momha_bwd_workspace_bytes(int B, int T, int k, int d_model, int h_expert, int d_head);
+int smoe_momha_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *dO, const void *X, int B, int T,
+                   int d_model, int h_expert, int d_head, const void *W_K, const void *W_V, const void *W_Q,
+                   const void *W_O, const smoe_routing *r, int k, const float *gates, const void *saved_K,
+                   const void *saved_V, const void *saved_Q, const void *saved_Ohat, const float *saved_LSE,
+                   const void *saved_Yhat, void *dX, void *dW_K, void *dW_V, void *dW_Q, void *dW_O,
+                   float *dgates, void *ws, size_t ws_bytes);
+
 #ifdef __cplusplus
 }
 #endif

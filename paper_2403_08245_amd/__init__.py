@@ -25,6 +25,7 @@ EXPORTS = [
     "smoe_plinear_fwd", "smoe_plinear_bwd_workspace_bytes", "smoe_plinear_bwd",
     "smoe_mlp_fwd_workspace_bytes", "smoe_mlp_fwd", "smoe_mlp_bwd_workspace_bytes", "smoe_mlp_bwd",
     "smoe_group", "smoe_attention_fwd", "smoe_attention_bwd_workspace_bytes", "smoe_attention_bwd",
+    "smoe_momha_fwd_workspace_bytes", "smoe_momha_fwd", "smoe_momha_bwd_workspace_bytes", "smoe_momha_bwd",
 ]
 
 
@@ -59,6 +60,14 @@ lib.smoe_attention_fwd.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, 
 lib.smoe_attention_bwd_workspace_bytes.argtypes = [_i, _i, _i, _i]
 lib.smoe_attention_bwd_workspace_bytes.restype = _sz
 lib.smoe_attention_bwd.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _sz]
+lib.smoe_momha_fwd_workspace_bytes.argtypes = [_i] * 7
+lib.smoe_momha_fwd_workspace_bytes.restype = _sz
+lib.smoe_momha_fwd.argtypes = [_vp, _vp, _i, _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _rp, _i, _vp, _vp,
+                               _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz]
+lib.smoe_momha_bwd_workspace_bytes.argtypes = [_i] * 6
+lib.smoe_momha_bwd_workspace_bytes.restype = _sz
+lib.smoe_momha_bwd.argtypes = [_vp, _vp, _i, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _rp, _i, _vp,
+                               _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz]
 lib.smoe_route_workspace_bytes.argtypes = [_i, _i, _i]
 lib.smoe_route_workspace_bytes.restype = _sz
 lib.smoe_route.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _sz]
@@ -192,6 +201,55 @@ def attention_bwd(dO, Q, K, V, O, LSE):
     _check(lib.smoe_attention_bwd(ctx(), _stream(), BF16, _p(dO), _p(Q), _p(K), _p(V), _p(O), _p(LSE), B, T, G, h, d,
                                   _p(dQ), _p(dK), _p(dV), _p(ws), nb), "smoe_attention_bwd")
     return dQ, dK, dV
+
+
+@dataclass
+class MomhaBuffers:
+    """Tensors smoe_momha_fwd keeps for the backward pass (Alg. 4's intermediates)."""
+    K: torch.Tensor
+    V: torch.Tensor
+    Q: torch.Tensor
+    Ohat: torch.Tensor
+    LSE: torch.Tensor
+    Yhat: torch.Tensor
+
+
+def momha_fwd(X, W_K, W_V, W_Q, W_O, r: Routing, k: int, gates, B: int, T: int, h_expert: int, d_head: int):
+    for t in (X, W_K, W_V, W_Q, W_O):
+        _chk(t, torch.bfloat16)
+    _chk(gates, torch.float32)
+    N, d_model = X.shape
+    d_out = h_expert * d_head
+    dev = X.device
+    bf = dict(dtype=torch.bfloat16, device=dev)
+    buf = MomhaBuffers(torch.empty(N, d_out, **bf), torch.empty(N, d_out, **bf), torch.empty(N * k, d_out, **bf),
+                       torch.empty(N * k, d_out, **bf), torch.empty(N * k, h_expert, dtype=torch.float32, device=dev),
+                       torch.empty(N * k, d_model, **bf))
+    O = torch.empty(N, d_model, **bf)
+    nb = lib.smoe_momha_fwd_workspace_bytes(B, T, k, d_model, h_expert, d_head, 1)
+    ws = _ws(nb, dev)
+    rc = r.c()
+    _check(lib.smoe_momha_fwd(ctx(), _stream(), BF16, _p(X), B, T, d_model, h_expert, d_head, _p(W_K), _p(W_V),
+                              _p(W_Q), _p(W_O), ctypes.byref(rc), k, _p(gates), _p(O), _p(buf.K), _p(buf.V),
+                              _p(buf.Q), _p(buf.Ohat), _p(buf.LSE), _p(buf.Yhat), _p(ws), nb), "smoe_momha_fwd")
+    return O, buf
+
+
+def momha_bwd(dO, X, W_K, W_V, W_Q, W_O, r: Routing, k: int, gates, B: int, T: int, h_expert: int, d_head: int,
+              buf: MomhaBuffers):
+    _chk(dO, torch.bfloat16)
+    N, d_model = X.shape
+    dX, dW_K, dW_V = torch.empty_like(X), torch.empty_like(W_K), torch.empty_like(W_V)
+    dW_Q, dW_O = torch.empty_like(W_Q), torch.empty_like(W_O)
+    dgates = torch.empty(N, k, dtype=torch.float32, device=X.device)
+    nb = lib.smoe_momha_bwd_workspace_bytes(B, T, k, d_model, h_expert, d_head)
+    ws = _ws(nb, X.device)
+    rc = r.c()
+    _check(lib.smoe_momha_bwd(ctx(), _stream(), BF16, _p(dO), _p(X), B, T, d_model, h_expert, d_head, _p(W_K), _p(W_V),
+                              _p(W_Q), _p(W_O), ctypes.byref(rc), k, _p(gates), _p(buf.K), _p(buf.V), _p(buf.Q),
+                              _p(buf.Ohat), _p(buf.LSE), _p(buf.Yhat), _p(dX), _p(dW_K), _p(dW_V), _p(dW_Q), _p(dW_O),
+                              _p(dgates), _p(ws), nb), "smoe_momha_bwd")
+    return dX, dW_K, dW_V, dW_Q, dW_O, dgates
 
 
 def route(expert_idxs: torch.Tensor, E: int) -> Routing:

@@ -394,4 +394,140 @@ int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
   return launch_combine(s, dtype, Xbar, nullptr, dX, T, k, d_model);                    // sum the k slots
 }
 
+// ------------------------------------------------------------------------------ Alg. 4
+namespace {
+struct MomhaSizes {
+  size_t kv, q, lse, yhat, x;   // bytes, each rounded up to 256
+};
+MomhaSizes momha_sizes(int B, int T, int k, int d_model, int h_expert, int d_head) {
+  size_t N = (size_t)B * T, Tk = N * k, d_out = (size_t)h_expert * d_head;
+  return MomhaSizes{align256(N * d_out * 2), align256(Tk * d_out * 2), align256(Tk * h_expert * sizeof(float)),
+                    align256(Tk * d_model * 2), align256(N * d_model * 2)};
+}
+int momha_args_ok(smoe_ctx *ctx, smoe_dtype dtype, int B, int T, int d_model, int h_expert, int d_head,
+                  const smoe_routing *r, int k) {
+  if (!ctx || !routing_ok(r) || d_model < 1 || k < 1) return SMOE_ERR_INVALID_ARG;
+  int rc = attention_args_ok(dtype, B, T, k, h_expert, d_head);
+  if (rc != SMOE_OK) return rc;
+  if ((long long)B * T * k != r->Tk) return SMOE_ERR_INVALID_ARG;
+  if (!width_ok(dtype, d_model)) return SMOE_ERR_UNSUPPORTED;
+  return SMOE_OK;
+}
+// a dense product A [n, d_in] x W (or W^T) run through the grouped kernels as one expert
+S2SArgs dense_s2s(const void *A, const void *W, void *C, const int32_t *offsets, int n, int d_in, int d_out, bool trans_w) {
+  smoe_routing r{nullptr, nullptr, offsets, n, 1};
+  return make_s2s(A, W, C, &r, d_in, d_out, trans_w, true, 1, true);
+}
+}  // namespace
+
+size_t smoe_momha_fwd_workspace_bytes(int B, int T, int k, int d_model, int h_expert, int d_head, int training) {
+  if (B < 1 || T < 1 || k < 1 || d_model < 1 || h_expert < 1 || d_head < 1) return 0;
+  MomhaSizes z = momha_sizes(B, T, k, d_model, h_expert, d_head);
+  return 256 + (training ? 0 : 2 * z.kv + 2 * z.q + z.lse + z.yhat);
+}
+
+int smoe_momha_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *X, int B, int T, int d_model,
+                   int h_expert, int d_head, const void *W_K, const void *W_V, const void *W_Q, const void *W_O,
+                   const smoe_routing *r, int k, const float *gates, void *O, void *saved_K, void *saved_V,
+                   void *saved_Q, void *saved_Ohat, float *saved_LSE, void *saved_Yhat, void *ws, size_t ws_bytes) {
+  int rc = momha_args_ok(ctx, dtype, B, T, d_model, h_expert, d_head, r, k);
+  if (rc != SMOE_OK) return rc;
+  if (!X || !W_K || !W_V || !W_Q || !W_O || !gates || !O) return SMOE_ERR_INVALID_ARG;
+  const int n_saved = !!saved_K + !!saved_V + !!saved_Q + !!saved_Ohat + !!saved_LSE + !!saved_Yhat;
+  if (n_saved != 0 && n_saved != 6) return SMOE_ERR_INVALID_ARG;
+  size_t need = smoe_momha_fwd_workspace_bytes(B, T, k, d_model, h_expert, d_head, n_saved == 6);
+  if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need) return SMOE_ERR_WORKSPACE;
+  const int N = B * T, Tk = r->Tk, d_out = h_expert * d_head;
+  MomhaSizes z = momha_sizes(B, T, k, d_model, h_expert, d_head);
+  char *p = (char *)ws;
+  int32_t *dense_off = (int32_t *)p;  p += 256;
+  if (n_saved == 0) {
+    saved_K = p;  p += z.kv;
+    saved_V = p;  p += z.kv;
+    saved_Q = p;  p += z.q;
+    saved_Ohat = p;  p += z.q;
+    saved_LSE = (float *)p;  p += z.lse;
+    saved_Yhat = p;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  rc = launch_dense_offsets(s, dense_off, N);
+  if (rc != SMOE_OK) return rc;
+  // V = X W_V, K = X W_K
+  rc = run_s2s(ctx, s, dtype, dense_s2s(X, W_V, saved_V, dense_off, N, d_model, d_out, false));
+  if (rc != SMOE_OK) return rc;
+  rc = run_s2s(ctx, s, dtype, dense_s2s(X, W_K, saved_K, dense_off, N, d_model, d_out, false));
+  if (rc != SMOE_OK) return rc;
+  // Q = ParallelLinear(X, W_Q, o, no p, scattered -> scattered)
+  rc = run_s2s(ctx, s, dtype, make_s2s(X, W_Q, saved_Q, r, d_model, d_out, false, false, k, false));
+  if (rc != SMOE_OK) return rc;
+  // Ohat = Attention(Q, K, V)
+  rc = launch_attn_fwd(s, saved_Q, saved_K, saved_V, saved_Ohat, saved_LSE, B, T, k, h_expert);
+  if (rc != SMOE_OK) return rc;
+  // O = ParallelLinear(Ohat, W_O, o, p, scattered -> scattered)
+  rc = run_s2s(ctx, s, dtype, make_s2s(saved_Ohat, W_O, saved_Yhat, r, d_out, d_model, false, false, 1, false));
+  if (rc != SMOE_OK) return rc;
+  return launch_combine(s, dtype, saved_Yhat, gates, O, N, k, d_model);
+}
+
+size_t smoe_momha_bwd_workspace_bytes(int B, int T, int k, int d_model, int h_expert, int d_head) {
+  if (B < 1 || T < 1 || k < 1 || d_model < 1 || h_expert < 1 || d_head < 1) return 0;
+  MomhaSizes z = momha_sizes(B, T, k, d_model, h_expert, d_head);
+  // dense offsets, dOhat, dQ, dK, dV, three partial dX, delta, and the ParallelLinear backward scratch
+  // (a grouped [Tk, d_model] and a grouped [Tk, d_out] array, used by both projections in turn)
+  return 256 + 2 * z.q + 2 * z.kv + 3 * z.x + z.lse + z.yhat + z.q;
+}
+
+int smoe_momha_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *dO, const void *X, int B, int T,
+                   int d_model, int h_expert, int d_head, const void *W_K, const void *W_V, const void *W_Q,
+                   const void *W_O, const smoe_routing *r, int k, const float *gates, const void *saved_K,
+                   const void *saved_V, const void *saved_Q, const void *saved_Ohat, const float *saved_LSE,
+                   const void *saved_Yhat, void *dX, void *dW_K, void *dW_V, void *dW_Q, void *dW_O, float *dgates,
+                   void *ws, size_t ws_bytes) {
+  int rc = momha_args_ok(ctx, dtype, B, T, d_model, h_expert, d_head, r, k);
+  if (rc != SMOE_OK) return rc;
+  if (!dO || !X || !W_K || !W_V || !W_Q || !W_O || !gates || !saved_K || !saved_V || !saved_Q || !saved_Ohat ||
+      !saved_LSE || !saved_Yhat || !dX || !dW_K || !dW_V || !dW_Q || !dW_O || !dgates)
+    return SMOE_ERR_INVALID_ARG;
+  size_t need = smoe_momha_bwd_workspace_bytes(B, T, k, d_model, h_expert, d_head);
+  if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need) return SMOE_ERR_WORKSPACE;
+  const int N = B * T, Tk = r->Tk, d_out = h_expert * d_head;
+  MomhaSizes z = momha_sizes(B, T, k, d_model, h_expert, d_head);
+  char *p = (char *)ws;
+  int32_t *dense_off = (int32_t *)p;  p += 256;
+  void *dOhat = p;  p += z.q;
+  void *dQ = p;     p += z.q;
+  void *dK = p;     p += z.kv;
+  void *dV = p;     p += z.kv;
+  void *dXq = p;    p += z.x;
+  void *dXk = p;    p += z.x;
+  void *dXv = p;    p += z.x;
+  float *delta = (float *)p;  p += z.lse;
+  void *sub = p;
+  const size_t sub_bytes = z.yhat + z.q;
+  hipStream_t s = (hipStream_t)stream;
+  rc = launch_dense_offsets(s, dense_off, N);
+  if (rc != SMOE_OK) return rc;
+  // output projection (Alg. 2 with p, scattered in with fan-out 1, scattered out): dOhat, dW_O, dp
+  rc = smoe_plinear_bwd(ctx, stream, dtype, dO, saved_Ohat, Tk, d_out, W_O, d_model, saved_Yhat, r, 1, gates, k, 0, 0,
+                        dOhat, dW_O, dgates, sub, sub_bytes);
+  if (rc != SMOE_OK) return rc;
+  rc = launch_attn_bwd(s, saved_Q, saved_K, saved_V, saved_Ohat, dOhat, saved_LSE, delta, dQ, dK, dV, B, T, k, h_expert);
+  if (rc != SMOE_OK) return rc;
+  // query projection (Alg. 2 without p, scattered in with fan-out k, scattered out): dX part, dW_Q
+  rc = smoe_plinear_bwd(ctx, stream, dtype, dQ, X, N, d_model, W_Q, d_out, nullptr, r, k, nullptr, 0, 0, 0, dXq, dW_Q,
+                        nullptr, sub, sub_bytes);
+  if (rc != SMOE_OK) return rc;
+  // dense key / value projections
+  DWArgs wk{X, dK, dW_K, dense_off, 1, N, d_model, d_out}, wv{X, dV, dW_V, dense_off, 1, N, d_model, d_out};
+  rc = run_dw(ctx, s, dtype, wk);
+  if (rc != SMOE_OK) return rc;
+  rc = run_dw(ctx, s, dtype, wv);
+  if (rc != SMOE_OK) return rc;
+  rc = run_s2s(ctx, s, dtype, dense_s2s(dK, W_K, dXk, dense_off, N, d_model, d_out, true));
+  if (rc != SMOE_OK) return rc;
+  rc = run_s2s(ctx, s, dtype, dense_s2s(dV, W_V, dXv, dense_off, N, d_model, d_out, true));
+  if (rc != SMOE_OK) return rc;
+  return launch_add3(s, dXq, dXk, dXv, dX, (size_t)N * d_model);
+}
+
 }  // extern "C"

@@ -46,6 +46,8 @@ int launch_attn_fwd(hipStream_t s, const void *Q, const void *K, const void *V, 
                     int h);
 int launch_attn_bwd(hipStream_t s, const void *Q, const void *K, const void *V, const void *O, const void *dO,
                     const float *LSE, float *delta, void *dQ, void *dK, void *dV, int B, int T, int G, int h);
+int launch_dense_offsets(hipStream_t s, int32_t *off, int n);
+int launch_add3(hipStream_t s, const void *a, const void *b, const void *c, void *out, size_t n);
 int launch_topk_gate_bwd(hipStream_t s, const int32_t *idx, const float *gates, const float *dgates, int T, int E, int k,
                          float *dlogits);
 size_t route_workspace_bytes(int Tk, int E);

@@ -239,3 +239,35 @@ static int rowdot_t(hipStream_t s, const void *dY, const void *Yhat, float *dg, 
 int launch_rowdot(hipStream_t s, smoe_dtype dt, const void *dY, const void *Yhat, float *dg, int Tk, int kp, int d) {
   return dt == SMOE_BF16 ? rowdot_t<bf16_t>(s, dY, Yhat, dg, Tk, kp, d) : rowdot_t<float>(s, dY, Yhat, dg, Tk, kp, d);
 }
+
+// ------------------------------------------------------------------------------------------
+// helpers of the attention layer: offsets of a single all-rows segment (a dense product run
+// through the grouped kernels as one expert), and the sum of three bf16 arrays
+// ------------------------------------------------------------------------------------------
+__global__ void dense_offsets_kernel(int32_t *off, int n) {
+  if (threadIdx.x == 0) { off[0] = 0; off[1] = n; }
+}
+int launch_dense_offsets(hipStream_t s, int32_t *off, int n) {
+  hipLaunchKernelGGL(dense_offsets_kernel, dim3(1), dim3(64), 0, s, off, n);
+  SMOE_LAUNCH_CHECK();
+  return SMOE_OK;
+}
+
+__global__ void __launch_bounds__(256) add3_kernel(const bf16_t *__restrict__ a, const bf16_t *__restrict__ b,
+                                                   const bf16_t *__restrict__ c, bf16_t *__restrict__ out, size_t n8) {
+  typedef bf16_t v8 __attribute__((ext_vector_type(8)));
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (size_t)gridDim.x * blockDim.x) {
+    v8 x = reinterpret_cast<const v8 *>(a)[i], y = reinterpret_cast<const v8 *>(b)[i], z = reinterpret_cast<const v8 *>(c)[i], r;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) r[q] = (bf16_t)((float)x[q] + (float)y[q] + (float)z[q]);
+    reinterpret_cast<v8 *>(out)[i] = r;
+  }
+}
+int launch_add3(hipStream_t s, const void *a, const void *b, const void *c, void *out, size_t n) {
+  if (n % 8) return SMOE_ERR_UNSUPPORTED;
+  if (!n) return SMOE_OK;
+  hipLaunchKernelGGL(add3_kernel, dim3(grid_for(n / 8)), dim3(256), 0, s, (const bf16_t *)a, (const bf16_t *)b,
+                     (const bf16_t *)c, (bf16_t *)out, n / 8);
+  SMOE_LAUNCH_CHECK();
+  return SMOE_OK;
+}

@@ -57,3 +57,112 @@ def test_attention_backward(smoe, B, T, G, h):
         err = _rel(got.float().cpu().numpy().astype(np.float64), ref)
         _log(f"  {name} rel err {err:.2e}")
         assert err <= TOL[torch.bfloat16], name
+
+
+def _layer_case(seed, B, T, d_model, E, k, h):
+    d_out = h * 128
+    N = B * T
+    X = _bf16((N, d_model), seed + 1)
+    W_K, W_V = _bf16((d_model, d_out), seed + 2, 0.05), _bf16((d_model, d_out), seed + 3, 0.05)
+    W_Q, W_O = _bf16((E, d_model, d_out), seed + 4, 0.05), _bf16((E, d_out, d_model), seed + 5, 0.05)
+    logits = torch.randn(N, E, generator=torch.Generator().manual_seed(seed + 6), dtype=torch.float32)
+    dO = _bf16((N, d_model), seed + 7)
+    return dict(X=X, W_K=W_K, W_V=W_V, W_Q=W_Q, W_O=W_O, logits=logits, dO=dO)
+
+
+def _run_layer(smoe, c, B, T, E, k, h, dO=None):
+    dev = lambda n: c[n].cuda()
+    ei, gates = smoe.topk_gate(c["logits"].cuda(), k)
+    r = smoe.route(ei, E)
+    O, buf = smoe.momha_fwd(dev("X"), dev("W_K"), dev("W_V"), dev("W_Q"), dev("W_O"), r, k, gates, B, T, h, 128)
+    grads = smoe.momha_bwd((c["dO"] if dO is None else dO).cuda(), dev("X"), dev("W_K"), dev("W_V"), dev("W_Q"),
+                           dev("W_O"), r, k, gates, B, T, h, 128, buf)
+    torch.cuda.synchronize()
+    return ei.cpu().numpy(), gates.cpu().numpy().astype(np.float64), O, buf, grads
+
+
+LAYER_SHAPES = [(2, 40, 64, 4, 2, 1), (2, 96, 256, 8, 4, 2), (1, 150, 128, 3, 3, 1)]
+
+
+@pytest.mark.parametrize("B,T,d_model,E,k,h", LAYER_SHAPES)
+def test_momha_layer_forward_and_backward(smoe, B, T, d_model, E, k, h):
+    """Alg. 4 end to end against the oracle (routing taken from the GPU's own bit-exact top-k)."""
+    _log(f"momha B={B} T={T} d_model={d_model} E={E} k={k} h={h}")
+    c = _layer_case(10 * T + E, B, T, d_model, E, k, h)
+    ei, g, O, buf, grads = _run_layer(smoe, c, B, T, E, k, h)
+    oei, og = oracle.topk_gate(c["logits"].numpy(), k)
+    assert np.array_equal(ei, oei)
+    args = [si.as_f64(c[n]) for n in ("X", "W_K", "W_V", "W_Q", "W_O")]
+    ref = oracle.momha_fwd(*args, oei, g, B, T, h, 128)
+    gref = oracle.momha_bwd(si.as_f64(c["dO"]), *args, oei, g, B, T, h, 128)
+    tol = TOL[torch.bfloat16]
+    f64 = lambda t: t.float().cpu().numpy().astype(np.float64)
+    for name, got, want in (("O", O, ref["O"]), ("K", buf.K, ref["K"]), ("V", buf.V, ref["V"]), ("Q", buf.Q, ref["Q"]),
+                            ("Ohat", buf.Ohat, ref["Ohat"]), ("Yhat", buf.Yhat, ref["Yhat"])):
+        err = _rel(f64(got), want)
+        _log(f"  {name} rel err {err:.2e}")
+        assert err <= tol, name
+    for name, got in zip(("dX", "dW_K", "dW_V", "dW_Q", "dW_O", "dgates"), grads):
+        err = _rel(f64(got), gref[name])
+        _log(f"  {name} rel err {err:.2e}")
+        assert err <= tol, name
+
+
+def test_momha_layer_C5_size_prefix_subproblem(smoe):
+    """Alg. 4 at the full C5 launch shape (2 x 4096 positions, d_model 2048, E 16, k 4, 4 heads of 128).
+    Causality makes the first P positions of every sequence a closed sub-problem: their outputs do not
+    depend on later positions, and with an upstream gradient that is zero after position P every
+    gradient equals the sub-problem's.  The oracle runs that sub-problem whole."""
+    B, T, d_model, E, k, h, P = 2, 4096, 2048, 16, 4, 4, 96
+    c = _layer_case(77, B, T, d_model, E, k, h)
+    keep = (torch.arange(B * T) % T) < P
+    dO = c["dO"].clone()
+    dO[~keep] = 0
+    ei, g, O, buf, grads = _run_layer(smoe, c, B, T, E, k, h, dO=dO)
+    _log("  GPU pass done")
+    oei, og = oracle.topk_gate(c["logits"].numpy(), k)
+    assert np.array_equal(ei, oei)
+    sel = keep.numpy()
+    args = [si.as_f64(c["X"])[sel]] + [si.as_f64(c[n]) for n in ("W_K", "W_V", "W_Q", "W_O")]
+    ref = oracle.momha_fwd(*args, oei[sel], g[sel], B, P, h, 128)
+    _log("  oracle forward done")
+    gref = oracle.momha_bwd(si.as_f64(dO)[sel], *args, oei[sel], g[sel], B, P, h, 128)
+    _log("  oracle backward done")
+    tol = TOL[torch.bfloat16]
+    f64 = lambda t: t.float().cpu().numpy().astype(np.float64)
+    assert _rel(f64(O)[sel], ref["O"]) <= tol
+    dX, dW_K, dW_V, dW_Q, dW_O, dg = grads
+    assert np.abs(f64(dX)[~sel]).max() == 0 and np.abs(f64(dg)[~sel]).max() == 0
+    for name, got, want in (("dX", f64(dX)[sel], gref["dX"]), ("dgates", f64(dg)[sel], gref["dgates"]),
+                            ("dW_K", f64(dW_K), gref["dW_K"]), ("dW_V", f64(dW_V), gref["dW_V"]),
+                            ("dW_Q", f64(dW_Q), gref["dW_Q"]), ("dW_O", f64(dW_O), gref["dW_O"])):
+        err = _rel(got, want)
+        _log(f"  {name} rel err {err:.2e}")
+        assert err <= tol, name
+
+
+def test_attention_C5_size_sampled_heads(smoe):
+    """Attention forward and backward at C5's shape, checked on sampled (sequence, slot, head) triples: one
+    slot's output and dQ involve only its own head's keys; dK/dV are checked with the upstream gradient
+    restricted to that slot so that they, too, come from a single triple."""
+    B, T, G, h = 2, 4096, 4, 4
+    Q, K, V = _bf16((B, T, G, h, 128), 21), _bf16((B, T, h, 128), 22), _bf16((B, T, h, 128), 23)
+    Qd, Kd, Vd = Q.cuda(), K.cuda(), V.cuda()
+    O, L = smoe.attention_fwd(Qd, Kd, Vd)
+    tol = TOL[torch.bfloat16]
+    for b, g, hh in ((0, 0, 0), (1, 3, 2), (0, 2, 3)):
+        _log(f"  triple {(b, g, hh)}")
+        q1, k1, v1 = si.as_f64(Q[b:b + 1, :, g:g + 1, hh:hh + 1]), si.as_f64(K[b:b + 1, :, hh:hh + 1]), si.as_f64(V[b:b + 1, :, hh:hh + 1])
+        Oref, Lref = oracle.attention_fwd(q1, k1, v1)
+        assert _rel(O[b, :, g, hh].float().cpu().numpy().astype(np.float64), Oref[0, :, 0, 0]) <= tol
+        assert np.abs(L[b, :, g, hh].cpu().numpy() - Lref[0, :, 0, 0]).max() <= 2e-2
+        dO = torch.zeros_like(Q)
+        dO[b, :, g, hh] = _bf16((T, 128), 30 + g)
+        dQ, dK, dV = smoe.attention_bwd(dO.cuda(), Qd, Kd, Vd, O, L)
+        rq, rk, rv = oracle.attention_bwd(si.as_f64(dO[b:b + 1, :, g:g + 1, hh:hh + 1]), q1, k1, v1)
+        assert _rel(dQ[b, :, g, hh].float().cpu().numpy().astype(np.float64), rq[0, :, 0, 0]) <= tol
+        assert _rel(dK[b, :, hh].float().cpu().numpy().astype(np.float64), rk[0, :, 0]) <= tol
+        assert _rel(dV[b, :, hh].float().cpu().numpy().astype(np.float64), rv[0, :, 0]) <= tol
+        other = dK.clone()
+        other[b, :, hh] = 0
+        assert other.abs().max().item() == 0          # no other head or sequence received a gradient
