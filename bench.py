@@ -133,6 +133,77 @@ def granularity_sweep(args):
         "dense_equal_active_parameters": dense, "sweep": rows}))
 
 
+def bench_momha(args):
+    """SMoE multi-head attention layer (Alg. 4) at the C5 shape: top-k + routing + layer forward + backward."""
+    import smoe_inputs as si
+    import paper_2403_08245_amd as smoe
+
+    m = si.MOA_C5
+    B, T, d_model, E, k, d_out = 2, m["T"] // 2, m["d_model"], m["E"], m["k"], m["d_out"]
+    h, d_head = d_out // 128, 128
+    N, Tk = B * T, B * T * k
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream()
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(args.seed)
+    draw = lambda shape, std, dt=torch.bfloat16: (torch.randn(*shape, generator=gen, device=dev) * std).to(dt)
+    X, dO = draw((N, d_model), 1.0), draw((N, d_model), 1.0)
+    W_K, W_V = draw((d_model, d_out), 0.02), draw((d_model, d_out), 0.02)
+    W_Q, W_O = draw((E, d_model, d_out), 0.02), draw((E, d_out, d_model), 0.02)
+    logits = draw((N, E), 1.0, torch.float32)
+
+    def fwd():
+        ei, gates = smoe.topk_gate(logits, k)
+        r = smoe.route(ei, E)
+        O, buf = smoe.momha_fwd(X, W_K, W_V, W_Q, W_O, r, k, gates, B, T, h, d_head)
+        return r, gates, buf
+
+    def step():
+        r, gates, buf = fwd()
+        smoe.momha_bwd(dO, X, W_K, W_V, W_Q, W_O, r, k, gates, B, T, h, d_head, buf)
+        return buf
+
+    def timed(fn, reps):
+        for _ in range(args.warmup):
+            out = fn()
+        ev = _events(reps + 1)
+        ev[0].record(stream)
+        for i in range(reps):
+            fn()
+            ev[i + 1].record(stream)
+        torch.cuda.synchronize()
+        return np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(reps)]), out
+
+    ts_f, _ = timed(fwd, args.steps)
+    t0 = time.perf_counter()
+    ts, buf = timed(step, args.steps)
+    Qh = buf.Q.view(B, T, k, h, d_head)
+    Kh, Vh = buf.K.view(B, T, h, d_head), buf.V.view(B, T, h, d_head)
+    ts_a, (Oh, L) = timed(lambda: smoe.attention_fwd(Qh, Kh, Vh), args.kernel_reps)
+    ts_ab, _ = timed(lambda: smoe.attention_bwd(Oh, Qh, Kh, Vh, Oh, L), args.kernel_reps)
+    pl = 2.0 * Tk * d_model * d_out * 2          # query and output ParallelLinears
+    dense = 2.0 * N * d_model * d_out * 2        # key and value projections
+    attn = 2.0 * 2.0 * B * h * (T * k) * ((T + 1) / 2.0) * d_head       # QK^T and PV over the causal half
+    flops = 3.0 * (pl + dense) + 3.5 * attn      # backward: two products per forward GEMM, five per attention pair
+    ms = float(np.median(ts))
+    ach = attn / (np.median(ts_a) * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "SMoE multi-head attention layer (Alg. 4) fwd+bwd throughput (routing + layer forward + backward)",
+        "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"C5: B={B} T={T} d_model={d_model} E={E} k={k} h_expert={h} d_head={d_head}, "
+                               "both ParallelLinears scattered->scattered, causal attention"},
+        "tokens_per_s": N / (ms * 1e-3),
+        "phases_ms": {"forward_with_routing": float(np.median(ts_f)), "attention_fwd": float(np.median(ts_a)),
+                      "attention_bwd": float(np.median(ts_ab))},
+        "flop": {"parallel_linears_fwd": pl, "dense_kv_fwd": dense, "attention_fwd": attn},
+        "roofline": {"bound": "mfma", "kernel": "attn_fwd_kernel (causal grouped-query attention)", "achieved": ach,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
+                     "ms_per_launch": float(np.median(ts_a)), "flop_per_launch": attn, "traffic": None}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -154,6 +225,8 @@ def main():
 
     if args.sweep == "granularity":
         return granularity_sweep(args)
+    if args.workload == "C5":
+        return bench_momha(args)
 
     import smoe_inputs as si
     import paper_2403_08245_amd as smoe

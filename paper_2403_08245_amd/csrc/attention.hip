@@ -19,6 +19,7 @@ constexpr int AKT = 32;             // keys (or query rows) per LDS tile
 constexpr int AROW = AD * 2;        // bytes per tile row
 constexpr int ATILE = AKT * AROW;   // 8 KB
 constexpr int AQ = 128;             // rows per block: 32 per wavefront
+constexpr int DKV_WAVES = 4;        // wavefronts (32 keys each) per block of the dK/dV kernel
 constexpr float NEG_BIG = -1.0e30f; // finite stand-in for -inf: exp2 of it is 0 and no inf - inf appears
 
 // 16-byte chunk swizzle of a 256-byte row: conflict free both for the row-per-lane reads
@@ -26,17 +27,19 @@ constexpr float NEG_BIG = -1.0e30f; // finite stand-in for -inf: exp2 of it is 0
 // 4 different 64-byte segments).
 __device__ __forceinline__ int a_swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
 
-// One wavefront's share (2 of 8 instructions) of loading a [32 x 128] tile whose row r comes
-// from `base + row_index(r) * ld`; rows past `last` repeat row `last`.
+// One wavefront's share (8 / NW instructions, NW wavefronts per block) of loading a [32 x 128]
+// tile whose row r comes from `base + row_index(r) * ld`; rows past `last` repeat row `last`.
+template <int NW = 4>
 __device__ __forceinline__ void load_tile_rows(const bf16_t *base, size_t ld, int row0, int last, uint32_t lds_tile,
                                                int wave, int uwave, int lane) {
+  constexpr int PER = 8 / NW;
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    int i = wave * 2 + u;
+  for (int u = 0; u < PER; ++u) {
+    int i = wave * PER + u;
     int row = 4 * i + (lane >> 4);
     int chunk = (lane & 15) ^ a_swz(row);
     int src = min(row0 + row, last);
-    load16_to_lds(base + (size_t)src * ld + chunk * 8, lds_tile + (uwave * 2 + u) * 1024);
+    load16_to_lds(base + (size_t)src * ld + chunk * 8, lds_tile + (uwave * PER + u) * 1024);
   }
 }
 
@@ -81,7 +84,7 @@ struct AttnDims {
 // ======================================================================================
 // forward: block = (query tile of 128 slot rows, head, sequence); keys stream through LDS
 // ======================================================================================
-__global__ void __launch_bounds__(256) attn_fwd_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+__global__ void __launch_bounds__(256, 2) attn_fwd_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                        const bf16_t *__restrict__ V, bf16_t *__restrict__ O,
                                                        float *__restrict__ LSE, AttnDims d) {
   __shared__ __attribute__((aligned(1024))) char smem[4 * ATILE];   // two stages of (K tile, V tile)
@@ -153,10 +156,12 @@ __global__ void __launch_bounds__(256) attn_fwd_kernel(const bf16_t *__restrict_
     }
     l = l * alpha + psum;
     m = m_new;
+    if (__any(alpha != 1.0f)) {   // wave-uniform: once the running maxima have settled nothing needs rescaling
 #pragma unroll
-    for (int f = 0; f < 4; ++f)
+      for (int f = 0; f < 4; ++f)
 #pragma unroll
-      for (int q = 0; q < 16; ++q) acc[f][q] *= alpha;
+        for (int q = 0; q < 16; ++q) acc[f][q] *= alpha;
+    }
     bf16x8 pb[2] = {pack8(s, 0), pack8(s, 1)};
 #pragma unroll
     for (int f = 0; f < 4; ++f)
@@ -292,12 +297,13 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const bf16_t *__restri
 }
 
 // ======================================================================================
-// backward, part 2: dK and dV.  Block = 128 keys of one (sequence, head), 32 per wavefront, a
+// backward, part 2: dK and dV.  Block = 32 * NW keys of one (sequence, head), 32 per wavefront, a
 // lane owns one key; the slot rows that can see them stream through LDS 32 at a time.
 //   S = Q K^T, P = exp2(S c - lse[row]), dV^T += dO^T P, dP = dO V^T,
 //   dS = P (dP - delta[row]) / sqrt(d), dK^T += Q^T dS
 // ======================================================================================
-__global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+template <int NW>
+__global__ void __launch_bounds__(64 * NW) attn_bwd_dkv_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                            const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
                                                            const float *__restrict__ LSE, const float *__restrict__ delta,
                                                            bf16_t *__restrict__ dK, bf16_t *__restrict__ dV, AttnDims d) {
@@ -308,7 +314,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const bf16_t *__restr
   const int kb = blockIdx.x;                                   // early keys have the long row lists
   const int hh = blockIdx.y, b = blockIdx.z;
   const int rows = d.T * d.G;
-  const int k0 = kb * AQ;
+  const int k0 = kb * 32 * NW;
   const int key = min(k0 + wave * 32 + (lane & 31), d.T - 1);
   const bool key_valid = k0 + wave * 32 + (lane & 31) < d.T;
   const int wave_key0 = k0 + wave * 32;
@@ -342,8 +348,8 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const bf16_t *__restr
       s_dlt[stage][threadIdx.x] = Db[(size_t)r * d.h];
     }
   };
-  load_tile_rows(Qb, d.ldq, t_first * AKT, rows - 1, lds0, wave, uwave, lane);
-  load_tile_rows(dOb, d.ldq, t_first * AKT, rows - 1, lds0 + ATILE, wave, uwave, lane);
+  load_tile_rows<NW>(Qb, d.ldq, t_first * AKT, rows - 1, lds0, wave, uwave, lane);
+  load_tile_rows<NW>(dOb, d.ldq, t_first * AKT, rows - 1, lds0 + ATILE, wave, uwave, lane);
   load_stats(t_first, 0);
   for (int j = 0; j < n_tiles; ++j) {
     wait_loads<0>();
@@ -351,8 +357,8 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_kernel(const bf16_t *__restr
     const int tile = t_first + j;
     if (j + 1 < n_tiles) {
       uint32_t nxt = lds0 + ((j + 1) & 1) * 2 * ATILE;
-      load_tile_rows(Qb, d.ldq, (tile + 1) * AKT, rows - 1, nxt, wave, uwave, lane);
-      load_tile_rows(dOb, d.ldq, (tile + 1) * AKT, rows - 1, nxt + ATILE, wave, uwave, lane);
+      load_tile_rows<NW>(Qb, d.ldq, (tile + 1) * AKT, rows - 1, nxt, wave, uwave, lane);
+      load_tile_rows<NW>(dOb, d.ldq, (tile + 1) * AKT, rows - 1, nxt + ATILE, wave, uwave, lane);
       load_stats(tile + 1, (j + 1) & 1);
     }
     const int r0 = tile * AKT;
@@ -434,7 +440,8 @@ int launch_attn_bwd(hipStream_t s, const void *Q, const void *K, const void *V, 
   hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(ceil_div(T * G, AQ), h, B), dim3(256), 0, s, (const bf16_t *)Q,
                      (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)dO, LSE, (const float *)delta, (bf16_t *)dQ, d);
   SMOE_LAUNCH_CHECK();
-  hipLaunchKernelGGL(attn_bwd_dkv_kernel, dim3(ceil_div(T, AQ), h, B), dim3(256), 0, s, (const bf16_t *)Q, (const bf16_t *)K,
+  constexpr int NW = DKV_WAVES;
+  hipLaunchKernelGGL(attn_bwd_dkv_kernel<NW>, dim3(ceil_div(T, 32 * NW), h, B), dim3(64 * NW), 0, s, (const bf16_t *)Q, (const bf16_t *)K,
                      (const bf16_t *)V, (const bf16_t *)dO, LSE, (const float *)delta, (bf16_t *)dK, (bf16_t *)dV, d);
   SMOE_LAUNCH_CHECK();
   return SMOE_OK;
