@@ -109,14 +109,14 @@ __device__ __forceinline__ void half_step(Ops &ops, const char *cur, const char 
       }
       // the source address of this group's load is worked out in the shadow of the matrix instructions
       const int I = kk * FR + g;
-      const bf16_t *src_ptr = ops.prepare(I);
+      const auto src = ops.prepare(I);
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
       }
       sched_fence();
-      load16_to_lds(src_ptr, fill + (I / NLD) * TILE_BYTES + inst_off(ops.uwave, I % NLD));
+      ops.issue(I, src, fill + (I / NLD) * TILE_BYTES + inst_off(ops.uwave, I % NLD));
       sched_fence();
     }
   }
@@ -132,15 +132,21 @@ struct S2STile {
 };
 
 template <bool TRANS_W> struct S2SStreamOps {
-  const bf16_t *pa[NLD], *pb[NLD];   // per-lane sources of the loader's current tile at contraction offset 0
-  size_t b_step;
+  // Sources of the loader's current tile: wave-uniform bases plus per-lane 32-bit byte offsets at
+  // contraction offset 0 (the launcher only takes this kernel when every offset fits 32 bits).
+  const char *base_a, *base_b;
+  uint32_t oa[NLD], ob[NLD];
+  uint32_t b_step;                   // bytes the W source moves per half-step
   int step;                          // half-step the next loads fetch
   int uwave;
-  __device__ __forceinline__ const bf16_t *prepare(int I) const {
-    return I < NLD ? pa[I] + (size_t)step * HK : pb[I - NLD] + (size_t)step * b_step;
+  __device__ __forceinline__ uint32_t prepare(int I) const {
+    return I < NLD ? oa[I] + (uint32_t)step * (HK * 2) : ob[I - NLD] + (uint32_t)step * b_step;
+  }
+  __device__ __forceinline__ void issue(int I, uint32_t off, uint32_t lds) const {
+    load16_to_lds(I < NLD ? base_a : base_b, off, lds);
   }
   __device__ __forceinline__ void load(int I, uint32_t tile_lds) {
-    load16_to_lds(prepare(I), tile_lds + inst_off(uwave, I % NLD));
+    issue(I, prepare(I), tile_lds + inst_off(uwave, I % NLD));
   }
   __device__ __forceinline__ bf16x8 frag_a(const char *tile, int base, int kk, int lane) {
     return kc_frag(tile, base, kk, lane);
@@ -198,22 +204,25 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
 
   S2SStreamOps<TRANS_W> ops;
   ops.uwave = uwave;
-  ops.b_step = TRANS_W ? (size_t)HK : (size_t)HK * a.ldw;
+  ops.b_step = TRANS_W ? (uint32_t)(HK * 2) : (uint32_t)(HK * 2) * (uint32_t)a.ldw;
   auto setup_pointers = [&](const S2STile &t) {
-    const bf16_t *W = (const bf16_t *)a.W + (size_t)t.e * a.w_stride;
+    ops.base_b = (const char *)((const bf16_t *)a.W + (size_t)t.e * a.w_stride);
+    // gathered rows are addressed from the start of A, expert-sorted rows from the tile's first row
+    ops.base_a = (const char *)(a.a_map.o ? A : A + (size_t)t.row0 * a.K);
     const int *idx = &s_idx[t.ord % 3][0];
+    const uint32_t row_bytes = (uint32_t)a.K * 2u;
 #pragma unroll
     for (int I = 0; I < NLD; ++I) {
       int r, c;
       kc_lane_slot(wave, lane, I, r, c);
-      int src;
+      uint32_t src;
       if (a.a_map.o) {
         uint32_t slot = (uint32_t)idx[r];
-        src = (int)(magic_a ? __umulhi(slot, magic_a) : slot);
+        src = magic_a ? __umulhi(slot, magic_a) : slot;
       } else {
-        src = min(t.row0 + r, t.row_end - 1);
+        src = (uint32_t)min(r, t.row_end - 1 - t.row0);
       }
-      ops.pa[I] = A + (size_t)src * a.K + c * 8;
+      ops.oa[I] = src * row_bytes + (uint32_t)c * 16u;
     }
 #pragma unroll
     for (int I = 0; I < NLD; ++I) {
@@ -221,12 +230,12 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
       if (TRANS_W) {
         kc_lane_slot(wave, lane, I, r, c);
         int n = min(t.n0 + r, a.N - 1);
-        ops.pb[I] = W + (size_t)n * a.ldw + c * 8;
+        ops.ob[I] = (uint32_t)n * (uint32_t)a.ldw * 2u + (uint32_t)c * 16u;
       } else {
         tr_lane_slot(wave, lane, I, r, c);
         int col = t.n0 + c * 8;
         if (col >= a.N) col = 0;
-        ops.pb[I] = W + (size_t)r * a.ldw + col;
+        ops.ob[I] = (uint32_t)r * (uint32_t)a.ldw * 2u + (uint32_t)col * 2u;
       }
     }
   };
@@ -348,6 +357,7 @@ struct DWStreamOps {
     const bf16_t *p = (is_a ? A : B) + (size_t)i * (is_a ? M : N) + col;
     return (real && i < row_end) ? p : (const bf16_t *)g_zero16;
   }
+  __device__ __forceinline__ void issue(int, const bf16_t *src, uint32_t lds) const { load16_to_lds(src, lds); }
   __device__ __forceinline__ void load(int I, uint32_t tile_lds) {
     load16_to_lds(prepare(I), tile_lds + inst_off(uwave, I % NLD));
   }
@@ -537,8 +547,13 @@ int launch_dw_stream_impl(hipStream_t s, const DWArgs &a) {
 // by the fan-out with a multiply-high that is exact while Tk * fan < 2^32.
 bool s2s_stream_supported(const S2SArgs &a) {
   long long fan = a.a_map.o ? a.a_map.fan : 1;
+  // every per-lane source offset (from the start of a gathered A, from a tile's first row of a
+  // sorted A, from the start of an expert's matrix) must fit the 32-bit offset of the loads
+  long long a_rows = a.a_map.o ? (long long)a.Tk / fan + 1 : TB;
+  long long w_rows = a.trans_w ? a.N : a.K;
   return a.K % HK == 0 && a.K >= 3 * HK && a.N % 8 == 0 && a.ldw % 8 == 0 && a.Tk > 0 && a.E <= MAX_E &&
-         (long long)a.Tk * fan < 0x100000000LL;
+         (long long)a.Tk * fan < 0x100000000LL && a_rows * a.K * 2 < 0x100000000LL &&
+         (w_rows + HK) * a.ldw * 2 < 0x100000000LL;
 }
 
 int launch_s2s_stream(hipStream_t s, const S2SArgs &a) {

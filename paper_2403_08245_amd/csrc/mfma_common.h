@@ -29,6 +29,13 @@ constexpr int FR = TB / 64;       // 32x32 fragments per wavefront along each ti
 __device__ __forceinline__ void load16_to_lds(const void *gsrc, uint32_t lds_addr) {
   __asm__ volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gsrc) : "memory", "m0");
 }
+// Same with the address split into a wave-uniform 64-bit base (scalar registers) and a 32-bit
+// per-lane byte offset: half the address registers go to the memory pipeline per instruction,
+// which shortens the issue of the load inside a matrix-instruction stream.
+__device__ __forceinline__ void load16_to_lds(const void *base, uint32_t byte_off, uint32_t lds_addr) {
+  __asm__ volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(byte_off), "s"(base)
+                   : "memory", "m0");
+}
 __device__ __forceinline__ void load4_to_lds(const void *gsrc, uint32_t lds_addr) {
   __asm__ volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(gsrc) : "memory", "m0");
 }
