@@ -35,48 +35,68 @@ __global__ void __launch_bounds__(256) topk_gate_kernel(const float *__restrict_
   for (int j = 0; j < k; ++j) gates[(size_t)t * k + j] *= inv;
 }
 
-// Same selection with one wavefront per token for E <= 64: lane e holds logit e, each of the k
-// rounds is a butterfly arg-max over (not yet taken, value descending, expert id ascending).
+// Same selection with one wavefront per token for E <= 64 * VPL, by ranking: lane x holds logits x,
+// x + 64, ...; the token's row sits in LDS and every lane counts, for each of its logits, how many
+// come before it in the order (value descending, expert id ascending).  A logit of rank r < k is slot r.
+template <int VPL>
 __global__ void __launch_bounds__(256) topk_gate_wave_kernel(const float *__restrict__ logits, int T, int E, int k,
                                                              int32_t *__restrict__ idx, float *__restrict__ gates) {
-  const int lane = threadIdx.x & 63;
-  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  __shared__ __attribute__((aligned(16))) float rows[4][64 * VPL];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t = blockIdx.x * 4 + wave;
   if (t >= T) return;
-  const bool has = lane < E;
-  float v = has ? logits[(size_t)t * E + lane] : 0.f;
-  bool avail = has;
-  float mine = 0.f, first_v = 0.f;   // lane j keeps the value picked in round j
-  int mine_i = -1;
-  for (int j = 0; j < k; ++j) {
-    float bv = v;
-    int bi = lane;
-    bool ba = avail;
+  float *row = rows[wave];
+  float v[VPL];
+  int rank[VPL];
 #pragma unroll
-    for (int d = 32; d > 0; d >>= 1) {
-      float ov = __shfl_xor(bv, d, 64);
-      int oi = __shfl_xor(bi, d, 64);
-      bool oa = __shfl_xor((int)ba, d, 64) != 0;
-      bool other_wins = oa && (!ba || ov > bv || (ov == bv && oi < bi));
-      if (other_wins) { bv = ov; bi = oi; ba = true; }
-    }
-    if (j == 0) first_v = bv;
-    if (lane == j) { mine = bv; mine_i = bi; }
-    if (lane == bi) avail = false;
+  for (int i = 0; i < VPL; ++i) {
+    int e = lane + 64 * i;
+    // padding ranks after every real logit and never before one (-inf loses ties to the lower real ids)
+    v[i] = e < E ? logits[(size_t)t * E + e] : -INFINITY;
+    row[e] = v[i];
+    rank[i] = 0;
   }
-  float w = (lane < k) ? expf(mine - first_v) : 0.f;
-  float sum = w;
+  const int E4 = (E + 3) & ~3;   // the row is read four logits at a time; entries up to 64 * VPL are initialised
+  for (int e0 = 0; e0 < E4; e0 += 4) {
+    const float4 o4 = *reinterpret_cast<const float4 *>(row + e0);   // same address in every lane: a broadcast read
+    const float o[4] = {o4.x, o4.y, o4.z, o4.w};
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+      for (int i = 0; i < VPL; ++i) rank[i] += (o[c] > v[i]) || (o[c] == v[i] && e0 + c < lane + 64 * i);
+  }
+  // the rank-0 logit is the maximum; the gates are the softmax over the k kept logits
+  float top = v[0];
+#pragma unroll
+  for (int i = 1; i < VPL; ++i) top = fmaxf(top, v[i]);
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) top = fmaxf(top, __shfl_xor(top, d, 64));
+  float w[VPL], sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < VPL; ++i) {
+    w[i] = (rank[i] < k && lane + 64 * i < E) ? expf(v[i] - top) : 0.f;
+    sum += w[i];
+  }
 #pragma unroll
   for (int d = 32; d > 0; d >>= 1) sum += __shfl_xor(sum, d, 64);
-  if (lane < k) {
-    idx[(size_t)t * k + lane] = mine_i;
-    gates[(size_t)t * k + lane] = w * (1.0f / sum);
-  }
+  const float inv = 1.0f / sum;
+#pragma unroll
+  for (int i = 0; i < VPL; ++i)
+    if (rank[i] < k && lane + 64 * i < E) {
+      idx[(size_t)t * k + rank[i]] = lane + 64 * i;
+      gates[(size_t)t * k + rank[i]] = w[i] * inv;
+    }
 }
 
 int launch_topk_gate(hipStream_t s, const float *logits, int T, int E, int k, int32_t *idx, float *gates) {
   if (T == 0) return SMOE_OK;
+  dim3 grid(ceil_div(T, 4)), block(256);
   if (E <= 64)
-    hipLaunchKernelGGL(topk_gate_wave_kernel, dim3(ceil_div(T, 4)), dim3(256), 0, s, logits, T, E, k, idx, gates);
+    hipLaunchKernelGGL(topk_gate_wave_kernel<1>, grid, block, 0, s, logits, T, E, k, idx, gates);
+  else if (E <= 128)
+    hipLaunchKernelGGL(topk_gate_wave_kernel<2>, grid, block, 0, s, logits, T, E, k, idx, gates);
+  else if (E <= 256)
+    hipLaunchKernelGGL(topk_gate_wave_kernel<4>, grid, block, 0, s, logits, T, E, k, idx, gates);
   else
     hipLaunchKernelGGL(topk_gate_kernel, dim3(ceil_div(T, 256)), dim3(256), 0, s, logits, T, E, k, idx, gates);
   SMOE_LAUNCH_CHECK();
@@ -129,7 +149,7 @@ static constexpr int ROUTE_CHUNK = 1024;  // slots per block
 __device__ __forceinline__ int clamp_expert(int e, int E) { return e < 0 ? 0 : (e >= E ? E - 1 : e); }
 
 __global__ void __launch_bounds__(64) route_count_kernel(const int32_t *__restrict__ expert_idxs, int Tk, int E,
-                                                         int32_t *__restrict__ counts /*[nchunk][E]*/) {
+                                                         int32_t *__restrict__ counts /*[E][nchunk]*/) {
   extern __shared__ int32_t hist[];
   for (int e = threadIdx.x; e < E; e += 64) hist[e] = 0;
   __syncthreads();
@@ -137,10 +157,11 @@ __global__ void __launch_bounds__(64) route_count_kernel(const int32_t *__restri
   int end = min(base + ROUTE_CHUNK, Tk);
   for (int s = base + threadIdx.x; s < end; s += 64) atomicAdd(&hist[clamp_expert(expert_idxs[s], E)], 1);
   __syncthreads();
-  for (int e = threadIdx.x; e < E; e += 64) counts[(size_t)blockIdx.x * E + e] = hist[e];
+  // expert-major so that the scan below reads each expert's chunk counts contiguously
+  for (int e = threadIdx.x; e < E; e += 64) counts[(size_t)e * gridDim.x + blockIdx.x] = hist[e];
 }
 
-// counts[c][e] -> start position of (c, e); offsets[e] = rows before expert e.  One wavefront
+// counts[e][c] -> start position of (chunk c, expert e); offsets[e] = rows before expert e.  One wavefront
 // per expert at a time: lanes take chunks, a wave prefix sum orders them.
 __global__ void __launch_bounds__(1024) route_scan_kernel(int32_t *__restrict__ counts, int nchunk, int E,
                                                           int32_t *__restrict__ offsets, int Tk) {
@@ -148,7 +169,7 @@ __global__ void __launch_bounds__(1024) route_scan_kernel(int32_t *__restrict__ 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwave = blockDim.x >> 6;
   for (int e = wave; e < E; e += nwave) {
     int sum = 0;
-    for (int c = lane; c < nchunk; c += 64) sum += counts[(size_t)c * E + e];
+    for (int c = lane; c < nchunk; c += 64) sum += counts[(size_t)e * nchunk + c];
 #pragma unroll
     for (int d = 32; d > 0; d >>= 1) sum += __shfl_xor(sum, d, 64);
     if (lane == 0) totals[e] = sum;
@@ -169,25 +190,25 @@ __global__ void __launch_bounds__(1024) route_scan_kernel(int32_t *__restrict__ 
     int run = totals[e];
     for (int c0 = 0; c0 < nchunk; c0 += 64) {
       int c = c0 + lane;
-      int n = (c < nchunk) ? counts[(size_t)c * E + e] : 0;
+      int n = (c < nchunk) ? counts[(size_t)e * nchunk + c] : 0;
       int incl = n;
 #pragma unroll
       for (int d = 1; d < 64; d <<= 1) {
         int up = __shfl_up(incl, d, 64);
         if (lane >= d) incl += up;
       }
-      if (c < nchunk) counts[(size_t)c * E + e] = run + incl - n;
+      if (c < nchunk) counts[(size_t)e * nchunk + c] = run + incl - n;
       run += __shfl(incl, 63, 64);
     }
   }
 }
 
 __global__ void __launch_bounds__(64) route_place_kernel(const int32_t *__restrict__ expert_idxs, int Tk, int E,
-                                                         const int32_t *__restrict__ starts /*[nchunk][E]*/,
+                                                         const int32_t *__restrict__ starts /*[E][nchunk]*/,
                                                          int32_t *__restrict__ sorted_e,
                                                          int32_t *__restrict__ sorted_s) {
   extern __shared__ int32_t next[];  // next free position per expert for this chunk
-  for (int e = threadIdx.x; e < E; e += 64) next[e] = starts[(size_t)blockIdx.x * E + e];
+  for (int e = threadIdx.x; e < E; e += 64) next[e] = starts[(size_t)e * gridDim.x + blockIdx.x];
   __syncthreads();
   int nbits = 32 - __clz(max(E - 1, 1));
   int base = blockIdx.x * ROUTE_CHUNK;

@@ -31,6 +31,7 @@ def _log(*a):
 ROUTING_CASES = [
     (1, 1, 1), (3, 4, 4), (64, 64, 8), (4, 64, 8), (256, 4, 2), (1000, 7, 3), (1023, 8, 1),
     (1025, 8, 2), (16384, 8, 2), (8192, 64, 8), (5000, 130, 5), (777, 1, 1),
+    (3000, 128, 16), (2000, 200, 70), (500, 256, 3), (300, 300, 4), (70000, 65, 2),
 ]
 
 
@@ -65,11 +66,12 @@ def test_router_gradient(smoe, T, E, k):
     assert (got[mask] == 0).all()                     # experts that were not kept get an exact zero
 
 
-def test_topk_ties_and_quantised_logits(smoe):
+@pytest.mark.parametrize("E,k", [(16, 4), (130, 9), (256, 70), (300, 5)])
+def test_topk_ties_and_quantised_logits(smoe, E, k):
     g = torch.Generator().manual_seed(5)
-    logits = torch.randint(-2, 3, (2048, 16), generator=g).to(torch.float32)     # many exact ties
-    ei, gates, se, o, off = oracle_routing(logits, 4, 16)
-    gi, gg = smoe.topk_gate(logits.cuda(), 4)
+    logits = torch.randint(-2, 3, (2048, E), generator=g).to(torch.float32)     # many exact ties
+    ei, gates, se, o, off = oracle_routing(logits, k, E)
+    gi, gg = smoe.topk_gate(logits.cuda(), k)
     assert np.array_equal(gi.cpu().numpy(), ei)
     assert np.abs(gg.cpu().numpy() - gates).max() <= 1e-6
 
