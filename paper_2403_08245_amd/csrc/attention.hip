@@ -302,7 +302,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const bf16_t *__restri
 //   S = Q K^T, P = exp2(S c - lse[row]), dV^T += dO^T P, dP = dO V^T,
 //   dS = P (dP - delta[row]) / sqrt(d), dK^T += Q^T dS
 // ======================================================================================
-template <int NW>
+template <int NW, bool DK, bool DV>
 __global__ void __launch_bounds__(64 * NW) attn_bwd_dkv_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                            const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
                                                            const float *__restrict__ LSE, const float *__restrict__ delta,
@@ -371,8 +371,10 @@ __global__ void __launch_bounds__(64 * NW) attn_bwd_dkv_kernel(const bf16_t *__r
     for (int q = 0; q < 16; ++q) { s[q] = 0.f; dp[q] = 0.f; }
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_rows_frag(qt, ks, lane), kf[ks], s, 0, 0, 0);
+    if (DK) {
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_rows_frag(dot, ks, lane), vf[ks], dp, 0, 0, 0);
+      for (int ks = 0; ks < 8; ++ks) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_rows_frag(dot, ks, lane), vf[ks], dp, 0, 0, 0);
+    }
     // rows of this tile that are earlier than the wavefront's last key, or past the end, need the mask
     const bool edge = (r0 / d.G < wave_key0 + 31) || (r0 + AKT > rows);
     f32x16 p;
@@ -400,8 +402,8 @@ __global__ void __launch_bounds__(64 * NW) attn_bwd_dkv_kernel(const bf16_t *__r
     for (int f = 0; f < 4; ++f)
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
-        accv[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cols_frag(dot, f * 32, s2, lane), pb[s2], accv[f], 0, 0, 0);
-        acck[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cols_frag(qt, f * 32, s2, lane), db[s2], acck[f], 0, 0, 0);
+        if (DV) accv[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cols_frag(dot, f * 32, s2, lane), pb[s2], accv[f], 0, 0, 0);
+        if (DK) acck[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cols_frag(qt, f * 32, s2, lane), db[s2], acck[f], 0, 0, 0);
       }
   }
   if (key_valid) {
@@ -412,8 +414,8 @@ __global__ void __launch_bounds__(64 * NW) attn_bwd_dkv_kernel(const bf16_t *__r
         bf16x4 vk, vv;
 #pragma unroll
         for (int c = 0; c < 4; ++c) { vk[c] = (bf16_t)acck[f][4 * g + c]; vv[c] = (bf16_t)accv[f][4 * g + c]; }
-        *reinterpret_cast<bf16x4 *>(dK + krow + f * 32 + 8 * g + 4 * (lane >> 5)) = vk;
-        *reinterpret_cast<bf16x4 *>(dV + krow + f * 32 + 8 * g + 4 * (lane >> 5)) = vv;
+        if (DK) *reinterpret_cast<bf16x4 *>(dK + krow + f * 32 + 8 * g + 4 * (lane >> 5)) = vk;
+        if (DV) *reinterpret_cast<bf16x4 *>(dV + krow + f * 32 + 8 * g + 4 * (lane >> 5)) = vv;
       }
   }
 }
@@ -441,7 +443,7 @@ int launch_attn_bwd(hipStream_t s, const void *Q, const void *K, const void *V, 
                      (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)dO, LSE, (const float *)delta, (bf16_t *)dQ, d);
   SMOE_LAUNCH_CHECK();
   constexpr int NW = DKV_WAVES;
-  hipLaunchKernelGGL(attn_bwd_dkv_kernel<NW>, dim3(ceil_div(T, 32 * NW), h, B), dim3(64 * NW), 0, s, (const bf16_t *)Q, (const bf16_t *)K,
+  hipLaunchKernelGGL((attn_bwd_dkv_kernel<NW, true, true>), dim3(ceil_div(T, 32 * NW), h, B), dim3(64 * NW), 0, s, (const bf16_t *)Q, (const bf16_t *)K,
                      (const bf16_t *)V, (const bf16_t *)dO, LSE, (const float *)delta, (bf16_t *)dK, (bf16_t *)dV, d);
   SMOE_LAUNCH_CHECK();
   return SMOE_OK;
