@@ -115,6 +115,48 @@ def granularity_sweep(args):
         return out
 
     dense = run(si.CONFIGS["G-dense"])
+
+    def vendor_dense():
+        """The same dense MLP with the vendor's GEMM (torch.matmul) and torch's GELU, for context only."""
+        cfg = si.CONFIGS["G-dense"]
+        X, dY = draw((cfg.T, cfg.d_model), 1.0), draw((cfg.T, cfg.d_model), 1.0)
+        W1, W2 = draw((cfg.d_model, cfg.d_expert), 0.02), draw((cfg.d_expert, cfg.d_model), 0.02)
+
+        def fwd():
+            hpre = X @ W1
+            return hpre, torch.nn.functional.gelu(hpre)
+
+        def fwd_only():
+            return fwd()[1] @ W2
+
+        def fwd_bwd():
+            hpre, hh = fwd()
+            _ = hh @ W2
+            dh = dY @ W2.t()
+            _ = hh.t() @ dY
+            t = hpre.float()
+            dhpre = (dh.float() * (0.5 * (1 + torch.erf(t * 0.7071067811865476))
+                                   + t * torch.exp(-0.5 * t * t) * 0.3989422804014327)).to(torch.bfloat16)
+            _ = X.t() @ dhpre
+            _ = dhpre @ W1.t()
+
+        out = {}
+        for name, fn in (("inference", fwd_only), ("training", fwd_bwd)):
+            for _ in range(args.warmup):
+                fn()
+            ev = _events(args.steps + 1)
+            ev[0].record(stream)
+            for i in range(args.steps):
+                fn()
+                ev[i + 1].record(stream)
+            torch.cuda.synchronize()
+            ts = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)])
+            flops = cfg.gemm_flops_fwd() * (1.0 if name == "inference" else 3.0)
+            out[name] = {"ms_median": float(np.median(ts)), "tflops": flops / (np.median(ts) * 1e-3) / 1e12}
+        return out
+
+    vendor = vendor_dense()
+    torch.cuda.empty_cache()
     rows = []
     for k in si.GRANULARITY_KS:
         cfg = si.CONFIGS[f"G{k}"]
@@ -130,7 +172,7 @@ def granularity_sweep(args):
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "granularity sweep: T=61440 d_model=4096 d_ff=8192 d_expert=d_ff/k E=8k act=gelu, "
                                "uniform router"},
-        "dense_equal_active_parameters": dense, "sweep": rows}))
+        "dense_equal_active_parameters": dense, "dense_vendor_gemm_context": vendor, "sweep": rows}))
 
 
 def bench_momha(args):
