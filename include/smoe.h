@@ -188,8 +188,9 @@ int smoe_attention_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void
 /* Backward of smoe_attention_fwd: gradients of O with respect to Q, K and V (same shapes and
  * dtype as the inputs), from the upstream dO [B, T, G, h, d_head] and the forward's O and LSE.
  * dK and dV sum over the G slots and the later positions that attend a key.  Deterministic
- * (no atomics: one pass owns the query rows, a second one the key rows).  The workspace holds
- * one fp32 per (slot row, head). */
+ * (no atomics: one pass owns the query rows; a second one owns the key rows, cut into chunks of
+ * slot rows whose fp32 partial sums a last kernel adds in a fixed order).  The workspace holds
+ * one fp32 per (slot row, head) and those partial sums. */
 size_t smoe_attention_bwd_workspace_bytes(int B, int T, int G, int h);
 int smoe_attention_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *dO, const void *Q,
                        const void *K, const void *V, const void *O, const float *LSE, int B, int T, int G,

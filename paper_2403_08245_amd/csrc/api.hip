@@ -119,7 +119,7 @@ int smoe_attention_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void
 
 size_t smoe_attention_bwd_workspace_bytes(int B, int T, int G, int h) {
   if (B < 1 || T < 1 || G < 1 || h < 1) return 0;
-  return align256((size_t)B * T * G * h * sizeof(float));
+  return align256(attn_bwd_workspace_bytes(B, T, G, h));
 }
 
 int smoe_attention_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *dO, const void *Q, const void *K,
@@ -129,7 +129,7 @@ int smoe_attention_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void
   int rc = attention_args_ok(dtype, B, T, G, h, d_head);
   if (rc != SMOE_OK) return rc;
   if (!ws || ((uintptr_t)ws & 255) || ws_bytes < smoe_attention_bwd_workspace_bytes(B, T, G, h)) return SMOE_ERR_WORKSPACE;
-  return launch_attn_bwd((hipStream_t)stream, Q, K, V, O, dO, LSE, (float *)ws, dQ, dK, dV, B, T, G, h);
+  return launch_attn_bwd((hipStream_t)stream, Q, K, V, O, dO, LSE, ws, dQ, dK, dV, B, T, G, h);
 }
 
 size_t smoe_route_workspace_bytes(int T, int k, int E) {
@@ -474,7 +474,7 @@ size_t smoe_momha_bwd_workspace_bytes(int B, int T, int k, int d_model, int h_ex
   MomhaSizes z = momha_sizes(B, T, k, d_model, h_expert, d_head);
   // dense offsets, dOhat, dQ, dK, dV, three partial dX, delta, and the ParallelLinear backward scratch
   // (a grouped [Tk, d_model] and a grouped [Tk, d_out] array, used by both projections in turn)
-  return 256 + 2 * z.q + 2 * z.kv + 3 * z.x + z.lse + z.yhat + z.q;
+  return 256 + 2 * z.q + 2 * z.kv + 3 * z.x + smoe_attention_bwd_workspace_bytes(B, T, k, h_expert) + z.yhat + z.q;
 }
 
 int smoe_momha_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *dO, const void *X, int B, int T,
@@ -501,7 +501,7 @@ int smoe_momha_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *dO
   void *dXq = p;    p += z.x;
   void *dXk = p;    p += z.x;
   void *dXv = p;    p += z.x;
-  float *delta = (float *)p;  p += z.lse;
+  void *attn_ws = p;  p += smoe_attention_bwd_workspace_bytes(B, T, k, h_expert);
   void *sub = p;
   const size_t sub_bytes = z.yhat + z.q;
   hipStream_t s = (hipStream_t)stream;
@@ -511,7 +511,7 @@ int smoe_momha_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *dO
   rc = smoe_plinear_bwd(ctx, stream, dtype, dO, saved_Ohat, Tk, d_out, W_O, d_model, saved_Yhat, r, 1, gates, k, 0, 0,
                         dOhat, dW_O, dgates, sub, sub_bytes);
   if (rc != SMOE_OK) return rc;
-  rc = launch_attn_bwd(s, saved_Q, saved_K, saved_V, saved_Ohat, dOhat, saved_LSE, delta, dQ, dK, dV, B, T, k, h_expert);
+  rc = launch_attn_bwd(s, saved_Q, saved_K, saved_V, saved_Ohat, dOhat, saved_LSE, attn_ws, dQ, dK, dV, B, T, k, h_expert);
   if (rc != SMOE_OK) return rc;
   // query projection (Alg. 2 without p, scattered in with fan-out k, scattered out): dX part, dW_Q
   rc = smoe_plinear_bwd(ctx, stream, dtype, dQ, X, N, d_model, W_Q, d_out, nullptr, r, k, nullptr, 0, 0, 0, dXq, dW_Q,

@@ -75,6 +75,20 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &p, int s) {
   return v;
 }
 
+// Split of the dK/dV pass: the slot rows that see key block kb (32 * NW keys) are cut into chunks of
+// `ch` 32-row tiles; a (key block, chunk) pair is one work unit.  Key blocks with a single chunk
+// store their gradients directly, the others leave fp32 partial sums that a second kernel adds
+// in chunk order (deterministic, no atomics).
+struct DkvPlan {
+  int ch;        // row tiles per chunk
+  int units;     // work units per (sequence, head)
+  int kblocks;   // key blocks per (sequence, head)
+};
+__host__ __device__ inline int dkv_first_tile(int kb, int keys_per_block, int G) { return (int)(((long long)kb * keys_per_block * G) / 32); }
+__host__ __device__ inline int dkv_chunks(int kb, int keys_per_block, int G, int row_tiles, int ch) {
+  return (row_tiles - dkv_first_tile(kb, keys_per_block, G) + ch - 1) / ch;
+}
+
 struct AttnDims {
   int B, T, G, h;
   size_t ldq, ldkv;    // row strides in elements: h * 128
@@ -306,14 +320,25 @@ template <int NW, bool DK, bool DV>
 __global__ void __launch_bounds__(64 * NW) attn_bwd_dkv_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                            const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
                                                            const float *__restrict__ LSE, const float *__restrict__ delta,
-                                                           bf16_t *__restrict__ dK, bf16_t *__restrict__ dV, AttnDims d) {
+                                                           bf16_t *__restrict__ dK, bf16_t *__restrict__ dV,
+                                                           float *__restrict__ part, DkvPlan plan, AttnDims d) {
   __shared__ __attribute__((aligned(1024))) char smem[4 * ATILE];
-  __shared__ __attribute__((aligned(16))) float s_lse[2][AKT], s_dlt[2][AKT];
+  // log-sum-exp and delta of the 32 rows of a tile; 64 entries per stage because a direct-to-LDS
+  // load always lands a whole wavefront's worth (the upper half repeats clamped rows, never read)
+  __shared__ __attribute__((aligned(256))) float s_lse[2][64], s_dlt[2][64];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int uwave = __builtin_amdgcn_readfirstlane(wave);
-  const int kb = blockIdx.x;                                   // early keys have the long row lists
   const int hh = blockIdx.y, b = blockIdx.z;
   const int rows = d.T * d.G;
+  const int row_tiles = (rows + AKT - 1) / AKT;
+  // work unit -> (key block, chunk of its row tiles)
+  int kb = 0, unit0 = 0, nch = dkv_chunks(0, 32 * NW, d.G, row_tiles, plan.ch);
+  while (unit0 + nch <= (int)blockIdx.x) {
+    unit0 += nch;
+    ++kb;
+    nch = dkv_chunks(kb, 32 * NW, d.G, row_tiles, plan.ch);
+  }
+  const int chunk = (int)blockIdx.x - unit0;
   const int k0 = kb * 32 * NW;
   const int key = min(k0 + wave * 32 + (lane & 31), d.T - 1);
   const bool key_valid = k0 + wave * 32 + (lane & 31) < d.T;
@@ -339,13 +364,18 @@ __global__ void __launch_bounds__(64 * NW) attn_bwd_dkv_kernel(const bf16_t *__r
 #pragma unroll
     for (int q = 0; q < 16; ++q) { acck[f][q] = 0.f; accv[f][q] = 0.f; }
 
-  const int t_first = (k0 * d.G) / AKT;                        // first 32-row tile holding a row that sees key k0
-  const int n_tiles = (rows + AKT - 1) / AKT - t_first;
+  // first 32-row tile of this unit (the key block's list starts at the tile holding the first row that sees key k0)
+  const int t_first = dkv_first_tile(kb, 32 * NW, d.G) + chunk * plan.ch;
+  const int n_tiles = min(plan.ch, row_tiles - t_first);
+  // the statistics travel like the tiles (direct-to-LDS): an ordinary load here would make the
+  // compiler wait for every outstanding load, the next tile's included, before its LDS store
+  const uint32_t lds_lse = __builtin_amdgcn_readfirstlane(lds_address((const char *)&s_lse[0][0]));
+  const uint32_t lds_dlt = __builtin_amdgcn_readfirstlane(lds_address((const char *)&s_dlt[0][0]));
   auto load_stats = [&](int tile, int stage) {
-    if (threadIdx.x < AKT) {
-      int r = min(tile * AKT + (int)threadIdx.x, rows - 1);
-      s_lse[stage][threadIdx.x] = Lb[(size_t)r * d.h] * 1.4426950408889634f;
-      s_dlt[stage][threadIdx.x] = Db[(size_t)r * d.h];
+    if (wave == 0) {
+      int r = min(tile * AKT + lane, rows - 1);
+      load4_to_lds(Lb + (size_t)r * d.h, lds_lse + stage * 256);
+      load4_to_lds(Db + (size_t)r * d.h, lds_dlt + stage * 256);
     }
   };
   load_tile_rows<NW>(Qb, d.ldq, t_first * AKT, rows - 1, lds0, wave, uwave, lane);
@@ -387,7 +417,7 @@ __global__ void __launch_bounds__(64 * NW) attn_bwd_dkv_kernel(const bf16_t *__r
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const int q = 4 * g + c;
-        float pv = __builtin_amdgcn_exp2f(s[q] * d.scale_log2 - lv[c]);
+        float pv = __builtin_amdgcn_exp2f(s[q] * d.scale_log2 - lv[c] * 1.4426950408889634f);
         if (edge) {
           int r = r0 + rr + c;
           if (r >= rows || r / d.G < key) pv = 0.f;
@@ -406,7 +436,19 @@ __global__ void __launch_bounds__(64 * NW) attn_bwd_dkv_kernel(const bf16_t *__r
         if (DK) acck[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cols_frag(qt, f * 32, s2, lane), db[s2], acck[f], 0, 0, 0);
       }
   }
-  if (key_valid) {
+  if (nch > 1) {   // partial sums of this chunk: [unit][dK | dV][key][128] fp32
+    float *pk = part + ((((size_t)b * d.h + hh) * plan.units + blockIdx.x) * 2) * (32 * NW) * AD +
+                (size_t)(wave * 32 + (lane & 31)) * AD;
+    float *pv = pk + (size_t)(32 * NW) * AD;
+#pragma unroll
+    for (int f = 0; f < 4; ++f)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = f * 32 + 8 * g + 4 * (lane >> 5);
+        if (DK) *reinterpret_cast<float4 *>(pk + col) = make_float4(acck[f][4 * g], acck[f][4 * g + 1], acck[f][4 * g + 2], acck[f][4 * g + 3]);
+        if (DV) *reinterpret_cast<float4 *>(pv + col) = make_float4(accv[f][4 * g], accv[f][4 * g + 1], accv[f][4 * g + 2], accv[f][4 * g + 3]);
+      }
+  } else if (key_valid) {
 #pragma unroll
     for (int f = 0; f < 4; ++f)
 #pragma unroll
@@ -417,6 +459,35 @@ __global__ void __launch_bounds__(64 * NW) attn_bwd_dkv_kernel(const bf16_t *__r
         if (DK) *reinterpret_cast<bf16x4 *>(dK + krow + f * 32 + 8 * g + 4 * (lane >> 5)) = vk;
         if (DV) *reinterpret_cast<bf16x4 *>(dV + krow + f * 32 + 8 * g + 4 * (lane >> 5)) = vv;
       }
+  }
+}
+
+// adds the chunk partials of one key block in chunk order and rounds once
+template <int NW>
+__global__ void __launch_bounds__(256) attn_bwd_dkv_reduce_kernel(const float *__restrict__ part, bf16_t *__restrict__ dK,
+                                                                  bf16_t *__restrict__ dV, DkvPlan plan, AttnDims d) {
+  const int kb = blockIdx.x, hh = blockIdx.y, b = blockIdx.z;
+  const int row_tiles = (d.T * d.G + AKT - 1) / AKT;
+  int unit0 = 0;
+  for (int i = 0; i < kb; ++i) unit0 += dkv_chunks(i, 32 * NW, d.G, row_tiles, plan.ch);
+  const int nch = dkv_chunks(kb, 32 * NW, d.G, row_tiles, plan.ch);
+  if (nch <= 1) return;
+  constexpr int KEYS = 32 * NW;
+  const float *base = part + (((size_t)b * d.h + hh) * plan.units + unit0) * 2 * KEYS * AD;
+  for (int i = threadIdx.x; i < 2 * KEYS * AD / 4; i += 256) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int c = 0; c < nch; ++c) {
+      const float4 v = reinterpret_cast<const float4 *>(base + (size_t)c * 2 * KEYS * AD)[i];
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    const int which = i / (KEYS * AD / 4), rem = i % (KEYS * AD / 4);
+    const int key = kb * KEYS + rem / (AD / 4), col = (rem % (AD / 4)) * 4;
+    if (key < d.T) {
+      bf16x4 o;
+      o[0] = (bf16_t)acc.x; o[1] = (bf16_t)acc.y; o[2] = (bf16_t)acc.z; o[3] = (bf16_t)acc.w;
+      bf16_t *dst = (which ? dV : dK) + ((size_t)b * d.T + key) * d.ldkv + hh * AD + col;
+      *reinterpret_cast<bf16x4 *>(dst) = o;
+    }
   }
 }
 
@@ -432,10 +503,28 @@ int launch_attn_fwd(hipStream_t s, const void *Q, const void *K, const void *V, 
   return SMOE_OK;
 }
 
+static DkvPlan dkv_plan(int T, int G) {
+  const int row_tiles = ceil_div(T * G, AKT), keys = 32 * DKV_WAVES;
+  DkvPlan p;
+  p.ch = row_tiles / 8 > 16 ? ceil_div(row_tiles, 8) : 16;   // the longest row list splits into about eight units
+  p.kblocks = ceil_div(T, keys);
+  p.units = 0;
+  for (int kb = 0; kb < p.kblocks; ++kb) p.units += dkv_chunks(kb, keys, G, row_tiles, p.ch);
+  return p;
+}
+
+size_t attn_bwd_workspace_bytes(int B, int T, int G, int h) {
+  DkvPlan p = dkv_plan(T, G);
+  size_t delta = ((size_t)B * T * G * h * sizeof(float) + 255) & ~(size_t)255;
+  return delta + (size_t)B * h * p.units * 2 * (32 * DKV_WAVES) * AD * sizeof(float);
+}
+
 int launch_attn_bwd(hipStream_t s, const void *Q, const void *K, const void *V, const void *O, const void *dO,
-                    const float *LSE, float *delta, void *dQ, void *dK, void *dV, int B, int T, int G, int h) {
+                    const float *LSE, void *ws, void *dQ, void *dK, void *dV, int B, int T, int G, int h) {
   AttnDims d{B, T, G, h, (size_t)h * AD, (size_t)h * AD, 1.4426950408889634f / sqrtf((float)AD)};
   size_t n = (size_t)B * T * G * h;
+  float *delta = (float *)ws;
+  float *part = (float *)((char *)ws + ((n * sizeof(float) + 255) & ~(size_t)255));
   hipLaunchKernelGGL(attn_delta_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, s, (const bf16_t *)O, (const bf16_t *)dO,
                      delta, n);
   SMOE_LAUNCH_CHECK();
@@ -443,8 +532,13 @@ int launch_attn_bwd(hipStream_t s, const void *Q, const void *K, const void *V, 
                      (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)dO, LSE, (const float *)delta, (bf16_t *)dQ, d);
   SMOE_LAUNCH_CHECK();
   constexpr int NW = DKV_WAVES;
-  hipLaunchKernelGGL((attn_bwd_dkv_kernel<NW, true, true>), dim3(ceil_div(T, 32 * NW), h, B), dim3(64 * NW), 0, s, (const bf16_t *)Q, (const bf16_t *)K,
-                     (const bf16_t *)V, (const bf16_t *)dO, LSE, (const float *)delta, (bf16_t *)dK, (bf16_t *)dV, d);
+  const DkvPlan plan = dkv_plan(T, G);
+  hipLaunchKernelGGL((attn_bwd_dkv_kernel<NW, true, true>), dim3(plan.units, h, B), dim3(64 * NW), 0, s, (const bf16_t *)Q,
+                     (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)dO, LSE, (const float *)delta, (bf16_t *)dK,
+                     (bf16_t *)dV, part, plan, d);
+  SMOE_LAUNCH_CHECK();
+  hipLaunchKernelGGL(attn_bwd_dkv_reduce_kernel<NW>, dim3(plan.kblocks, h, B), dim3(256), 0, s, (const float *)part,
+                     (bf16_t *)dK, (bf16_t *)dV, plan, d);
   SMOE_LAUNCH_CHECK();
   return SMOE_OK;
 }

@@ -44,8 +44,9 @@ __device__ __forceinline__ int map_row(const RowMap &m, int i) {
 int launch_topk_gate(hipStream_t s, const float *logits, int T, int E, int k, int32_t *idx, float *gates);
 int launch_attn_fwd(hipStream_t s, const void *Q, const void *K, const void *V, void *O, float *LSE, int B, int T, int G,
                     int h);
+size_t attn_bwd_workspace_bytes(int B, int T, int G, int h);
 int launch_attn_bwd(hipStream_t s, const void *Q, const void *K, const void *V, const void *O, const void *dO,
-                    const float *LSE, float *delta, void *dQ, void *dK, void *dV, int B, int T, int G, int h);
+                    const float *LSE, void *ws, void *dQ, void *dK, void *dV, int B, int T, int G, int h);
 int launch_dense_offsets(hipStream_t s, int32_t *off, int n);
 int launch_add3(hipStream_t s, const void *a, const void *b, const void *c, void *out, size_t n);
 int launch_topk_gate_bwd(hipStream_t s, const int32_t *idx, const float *gates, const float *dgates, int T, int E, int k,
