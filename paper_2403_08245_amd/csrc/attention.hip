@@ -317,12 +317,13 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const bf16_t *__restri
 //   dS = P (dP - delta[row]) / sqrt(d), dK^T += Q^T dS
 // ======================================================================================
 template <int NW, bool DK, bool DV>
-__global__ void __launch_bounds__(64 * NW) attn_bwd_dkv_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+__global__ void __launch_bounds__(64 * NW, 2) attn_bwd_dkv_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                            const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
                                                            const float *__restrict__ LSE, const float *__restrict__ delta,
                                                            bf16_t *__restrict__ dK, bf16_t *__restrict__ dV,
                                                            float *__restrict__ part, DkvPlan plan, AttnDims d) {
   __shared__ __attribute__((aligned(1024))) char smem[4 * ATILE];
+  __shared__ __attribute__((aligned(1024))) char s_v[NW * ATILE];   // the block's own V rows, 32 per wavefront
   // log-sum-exp and delta of the 32 rows of a tile; 64 entries per stage because a direct-to-LDS
   // load always lands a whole wavefront's worth (the upper half repeats clamped rows, never read)
   __shared__ __attribute__((aligned(256))) float s_lse[2][64], s_dlt[2][64];
@@ -345,12 +346,14 @@ __global__ void __launch_bounds__(64 * NW) attn_bwd_dkv_kernel(const bf16_t *__r
   const int wave_key0 = k0 + wave * 32;
 
   const size_t krow = ((size_t)b * d.T + key) * d.ldkv + hh * AD;
-  bf16x8 kf[8], vf[8];
+  // K fragments stay in registers; the V fragments are re-read from LDS at every use (keeping both
+  // in registers pushes the kernel past 256 registers and down to one wavefront per SIMD)
+  bf16x8 kf[8];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    kf[ks] = *reinterpret_cast<const bf16x8 *>(K + krow + 16 * ks + 8 * (lane >> 5));
-    vf[ks] = *reinterpret_cast<const bf16x8 *>(V + krow + 16 * ks + 8 * (lane >> 5));
-  }
+  for (int ks = 0; ks < 8; ++ks) kf[ks] = *reinterpret_cast<const bf16x8 *>(K + krow + 16 * ks + 8 * (lane >> 5));
+  const char *vmine = s_v + wave * ATILE;
+  load_tile_rows<1>(V + (size_t)b * d.T * d.ldkv + hh * AD, d.ldkv, wave_key0, d.T - 1,
+                    __builtin_amdgcn_readfirstlane(lds_address(s_v)) + uwave * ATILE, 0, 0, lane);
   const bf16_t *Qb = Q + (size_t)b * rows * d.ldq + hh * AD;
   const bf16_t *dOb = dO + (size_t)b * rows * d.ldq + hh * AD;
   const float *Lb = LSE + (size_t)b * rows * d.h + hh;
@@ -403,7 +406,8 @@ __global__ void __launch_bounds__(64 * NW) attn_bwd_dkv_kernel(const bf16_t *__r
     for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_rows_frag(qt, ks, lane), kf[ks], s, 0, 0, 0);
     if (DK) {
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_rows_frag(dot, ks, lane), vf[ks], dp, 0, 0, 0);
+      for (int ks = 0; ks < 8; ++ks)
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_rows_frag(dot, ks, lane), a_rows_frag(vmine, ks, lane), dp, 0, 0, 0);
     }
     // rows of this tile that are earlier than the wavefront's last key, or past the end, need the mask
     const bool edge = (r0 / d.G < wave_key0 + 31) || (r0 + AKT > rows);
