@@ -39,6 +39,7 @@ S2SArgs make_s2s(const void *A, const void *W, void *C, const smoe_routing *r, i
   a.ldw = d_out;
   a.w_stride = (size_t)d_in * d_out;
   a.trans_w = trans_w ? 1 : 0;
+  a.H = nullptr;
   return a;
 }
 }  // namespace
@@ -308,13 +309,23 @@ int smoe_mlp_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
       !aligned16(saved_H) || !aligned16(saved_Yhat))
     return SMOE_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
-  // Hpre = ParallelLinear(X, W1, scattered -> grouped)
+  // Hpre = ParallelLinear(X, W1, scattered -> grouped);  H = sigma(Hpre)
   S2SArgs a1 = make_s2s(X, W1, saved_Hpre, r, d_model, d_h, false, false, k, true);
-  int rc = run_s2s(ctx, s, dtype, a1);
-  if (rc != SMOE_OK) return rc;
-  // H = sigma(Hpre)
-  rc = launch_act_fwd(s, dtype, act, saved_Hpre, saved_H, Tk, d_expert);
-  if (rc != SMOE_OK) return rc;
+  int rc;
+  S2SArgs fused = a1;
+  fused.H = saved_H;
+  if (act == SMOE_ACT_SWIGLU && dtype == SMOE_BF16 && ctx->kernel_mode == 0 && s2s_stream_swiglu_supported(fused)) {
+    // SwiGLU in the product's epilogue: H comes straight from the fp32 accumulators, and the
+    // pre-activation is written only when the caller keeps it for the backward pass
+    if (nsaved == 0) fused.C = nullptr;
+    rc = launch_s2s_stream(s, fused);
+    if (rc != SMOE_OK) return rc;
+  } else {
+    rc = run_s2s(ctx, s, dtype, a1);
+    if (rc != SMOE_OK) return rc;
+    rc = launch_act_fwd(s, dtype, act, saved_Hpre, saved_H, Tk, d_expert);
+    if (rc != SMOE_OK) return rc;
+  }
   // Y = ParallelLinear(H, W2, p, grouped -> scattered)
   S2SArgs a2 = make_s2s(saved_H, W2, saved_Yhat, r, d_expert, d_model, false, true, 1, false);
   rc = run_s2s(ctx, s, dtype, a2);

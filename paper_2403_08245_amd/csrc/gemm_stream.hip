@@ -73,6 +73,68 @@ __device__ __forceinline__ void store_wave_tile(const f32x16 (&acc)[FR][FR], cha
   }
 }
 
+// Epilogue of a SwiGLU tile: the wavefront's 128 accumulator columns are 64 gate columns (fragments 0, 1)
+// and the 64 up columns that pair with them (fragments 2, 3), so a lane holds both factors of each hidden
+// unit in matching registers.  Writes the pre-activation halves (KEEP) and H = silu(gate) * up, each
+// through the same 32 x 64 LDS patch as above and as straight-line code.  gcol is the first gate column
+// of this wavefront, half_n the number of gate columns of the layer.
+template <typename RowFn>
+__device__ __forceinline__ void flush_patch(const char *patch, RowFn dst_row, int fm, bf16_t *dst_base, size_t ld, int col0,
+                                            int gcol, int half_n, int lane) {
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    int r = it * 8 + (lane >> 3);
+    int chunk = lane & 7;
+    bf16x8 v = *reinterpret_cast<const bf16x8 *>(patch + r * EPI_ROW_BYTES + chunk * 16);
+    int dst = dst_row(fm * 32 + r);
+    int col = gcol + chunk * 8;
+    bf16_t *p = (dst >= 0 && col < half_n) ? dst_base + (size_t)dst * ld + col0 + col : (bf16_t *)g_trash + lane * 8;
+    *reinterpret_cast<bf16x8 *>(p) = v;
+  }
+}
+
+template <bool KEEP, typename RowFn>
+__device__ __forceinline__ void store_wave_tile_swiglu(const f32x16 (&acc)[FR][FR], char *patch, RowFn dst_row, bf16_t *C,
+                                                       bf16_t *H, int half_n, int gcol, int lane) {
+  __asm__ volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+  for (int fm = 0; fm < FR; ++fm) {
+    if (KEEP) {
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {   // gate columns, then up columns of the pre-activation
+        sched_fence();
+#pragma unroll
+        for (int f2 = 0; f2 < 2; ++f2)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            bf16x4 v;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = (bf16_t)acc_read(acc[fm][half * 2 + f2][g * 4 + q]);
+            int col = f2 * 32 + 8 * g + 4 * (lane >> 5);
+            *reinterpret_cast<bf16x4 *>(patch + (lane & 31) * EPI_ROW_BYTES + col * 2) = v;
+          }
+        flush_patch(patch, dst_row, fm, C, (size_t)2 * half_n, half * half_n, gcol, half_n, lane);
+      }
+    }
+    sched_fence();
+#pragma unroll
+    for (int f2 = 0; f2 < 2; ++f2)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        bf16x4 v;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          float gate = acc_read(acc[fm][f2][g * 4 + q]), up = acc_read(acc[fm][2 + f2][g * 4 + q]);
+          float sig = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gate));
+          v[q] = (bf16_t)(gate * sig * up);
+        }
+        int col = f2 * 32 + 8 * g + 4 * (lane >> 5);
+        *reinterpret_cast<bf16x4 *>(patch + (lane & 31) * EPI_ROW_BYTES + col * 2) = v;
+      }
+    flush_patch(patch, dst_row, fm, H, (size_t)half_n, 0, gcol, half_n, lane);
+  }
+}
+
 // One half-step of the contraction: 32 matrix instructions on the landed stage `cur`, the
 // fragment reads of its second half and of the next stage's first half riding behind them, and
 // the eight loads of the stage being refilled, one per four matrix instructions.  FIRST starts
@@ -156,9 +218,11 @@ template <bool TRANS_W> struct S2SStreamOps {
   }
 };
 
-template <bool TRANS_W, bool SCATTER_OUT>
+template <bool TRANS_W, bool SCATTER_OUT, int ACT = 0>   // ACT 1: fused SwiGLU keeping the pre-activation, 2: without
 __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int tiles_n, int group_m, int total_vids,
                                                                  uint32_t magic_a) {
+  static_assert(ACT == 0 || (!TRANS_W && !SCATTER_OUT), "the fused activation belongs to the forward, sorted-output product");
+  constexpr bool SWIGLU = ACT != 0;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   __shared__ int s_off[MAX_E + 1];
   __shared__ int s_idx[3][TB];   // order indices of the rows of up to three open tiles
@@ -190,7 +254,7 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
         t.e = __builtin_amdgcn_readfirstlane(e);
         t.row0 = __builtin_amdgcn_readfirstlane(row0);
         t.row_end = __builtin_amdgcn_readfirstlane(row_end);
-        t.n0 = nt * TB;
+        t.n0 = nt * (SWIGLU ? TB / 2 : TB);   // SwiGLU tiles hold 128 gate columns and the 128 up columns pairing with them
         return true;
       }
     }
@@ -234,6 +298,11 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
       } else {
         tr_lane_slot(wave, lane, I, r, c);
         int col = t.n0 + c * 8;
+        if (SWIGLU) {
+          // tile column v = c * 8: wavefront column half v / 128 takes 64 gate columns then their 64 up columns
+          const int v = c * 8, w = v & 127, gate = t.n0 + (v >> 7) * 64 + (w & 63);
+          col = (gate < a.N / 2) ? gate + (w >> 6) * (a.N / 2) : a.N;
+        }
         if (col >= a.N) col = 0;
         ops.ob[I] = (uint32_t)r * (uint32_t)a.ldw * 2u + (uint32_t)col * 2u;
       }
@@ -316,7 +385,10 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
       int row = SCATTER_OUT ? idx[r] : i;
       return (i < ct.row_end) ? row : -1;
     };
-    store_wave_tile(acc, patch, dst_row, (bf16_t *)a.C, a.N, ct.n0 + wn * (TB / 2), a.N, lane);
+    if (SWIGLU)
+      store_wave_tile_swiglu<ACT == 1>(acc, patch, dst_row, (bf16_t *)a.C, (bf16_t *)a.H, a.N / 2, ct.n0 + wn * (TB / 4), lane);
+    else
+      store_wave_tile(acc, patch, dst_row, (bf16_t *)a.C, a.N, ct.n0 + wn * (TB / 2), a.N, lane);
     if (!next_tile(ct)) break;
   }
   wait_loads<0>();
@@ -517,15 +589,15 @@ template <typename K> int set_lds_limit(K kernel, int bytes) {
 
 uint32_t division_magic(int fan) { return fan > 1 ? (uint32_t)((0x100000000ULL + fan - 1) / fan) : 0u; }
 
-template <bool TRANS_W, bool SCATTER_OUT> int launch_s2s_stream_cfg(hipStream_t s, const S2SArgs &a) {
-  static int attr_rc = set_lds_limit(s2s_stream_kernel<TRANS_W, SCATTER_OUT>, STREAM_LDS_BYTES);
+template <bool TRANS_W, bool SCATTER_OUT, int ACT = 0> int launch_s2s_stream_cfg(hipStream_t s, const S2SArgs &a) {
+  static int attr_rc = set_lds_limit(s2s_stream_kernel<TRANS_W, SCATTER_OUT, ACT>, STREAM_LDS_BYTES);
   if (attr_rc != SMOE_OK) return attr_rc;
-  int tiles_n = ceil_div(a.N, TB);
+  int tiles_n = ACT ? ceil_div(a.N / 2, TB / 2) : ceil_div(a.N, TB);
   int tiles_m = ceil_div(a.Tk, TB) + a.E;     // upper bound on sum_e ceil(n_e / 256)
   int group_m = 4;
   long long total = (long long)ceil_div(tiles_m, group_m) * group_m * tiles_n;
   if (total > 0x7fffffffLL) return SMOE_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL((s2s_stream_kernel<TRANS_W, SCATTER_OUT>), dim3(STREAM_GRID), dim3(NTHREADS), STREAM_LDS_BYTES, s, a, tiles_n,
+  hipLaunchKernelGGL((s2s_stream_kernel<TRANS_W, SCATTER_OUT, ACT>), dim3(STREAM_GRID), dim3(NTHREADS), STREAM_LDS_BYTES, s, a, tiles_n,
                      group_m, (int)total, division_magic(a.a_map.o ? a.a_map.fan : 1));
   SMOE_LAUNCH_CHECK();
   return SMOE_OK;
@@ -556,8 +628,16 @@ bool s2s_stream_supported(const S2SArgs &a) {
          (w_rows + HK) * a.ldw * 2 < 0x100000000LL;
 }
 
+bool s2s_stream_swiglu_supported(const S2SArgs &a) {
+  return s2s_stream_supported(a) && !a.trans_w && !a.c_map.o && a.H && a.N % 16 == 0;
+}
+
 int launch_s2s_stream(hipStream_t s, const S2SArgs &a) {
   const bool scatter_out = a.c_map.o != nullptr;
+  if (a.H) {
+    if (!s2s_stream_swiglu_supported(a)) return SMOE_ERR_UNSUPPORTED;
+    return a.C ? launch_s2s_stream_cfg<false, false, 1>(s, a) : launch_s2s_stream_cfg<false, false, 2>(s, a);
+  }
   if (a.trans_w) return scatter_out ? launch_s2s_stream_cfg<true, true>(s, a) : launch_s2s_stream_cfg<true, false>(s, a);
   return scatter_out ? launch_s2s_stream_cfg<false, true>(s, a) : launch_s2s_stream_cfg<false, false>(s, a);
 }
