@@ -470,7 +470,8 @@ __global__ void __launch_bounds__(64 * NW, 2) attn_bwd_dkv_kernel(const bf16_t *
 template <int NW>
 __global__ void __launch_bounds__(256) attn_bwd_dkv_reduce_kernel(const float *__restrict__ part, bf16_t *__restrict__ dK,
                                                                   bf16_t *__restrict__ dV, DkvPlan plan, AttnDims d) {
-  const int kb = blockIdx.x, hh = blockIdx.y, b = blockIdx.z;
+  constexpr int SPLIT = 8;   // blocks per key block
+  const int kb = blockIdx.x / SPLIT, part_id = blockIdx.x % SPLIT, hh = blockIdx.y, b = blockIdx.z;
   const int row_tiles = (d.T * d.G + AKT - 1) / AKT;
   int unit0 = 0;
   for (int i = 0; i < kb; ++i) unit0 += dkv_chunks(i, 32 * NW, d.G, row_tiles, plan.ch);
@@ -478,7 +479,8 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_reduce_kernel(const float *_
   if (nch <= 1) return;
   constexpr int KEYS = 32 * NW;
   const float *base = part + (((size_t)b * d.h + hh) * plan.units + unit0) * 2 * KEYS * AD;
-  for (int i = threadIdx.x; i < 2 * KEYS * AD / 4; i += 256) {
+  constexpr int PER = 2 * KEYS * AD / 4 / SPLIT;
+  for (int i = part_id * PER + threadIdx.x; i < (part_id + 1) * PER; i += 256) {
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int c = 0; c < nch; ++c) {
       const float4 v = reinterpret_cast<const float4 *>(base + (size_t)c * 2 * KEYS * AD)[i];
@@ -541,7 +543,7 @@ int launch_attn_bwd(hipStream_t s, const void *Q, const void *K, const void *V, 
                      (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)dO, LSE, (const float *)delta, (bf16_t *)dK,
                      (bf16_t *)dV, part, plan, d);
   SMOE_LAUNCH_CHECK();
-  hipLaunchKernelGGL(attn_bwd_dkv_reduce_kernel<NW>, dim3(plan.kblocks, h, B), dim3(256), 0, s, (const float *)part,
+  hipLaunchKernelGGL(attn_bwd_dkv_reduce_kernel<NW>, dim3(plan.kblocks * 8, h, B), dim3(256), 0, s, (const float *)part,
                      (bf16_t *)dK, (bf16_t *)dV, plan, d);
   SMOE_LAUNCH_CHECK();
   return SMOE_OK;
