@@ -180,8 +180,14 @@ def bench_momha(args):
     import smoe_inputs as si
     import paper_2403_08245_amd as smoe
 
-    m = si.MOA_C5
-    B, T, d_model, E, k, d_out = 2, m["T"] // 2, m["d_model"], m["E"], m["k"], m["d_out"]
+    if args.workload == "C5":
+        m = si.MOA_C5
+        B, T, d_model, E, k, d_out = 2, m["T"] // 2, m["d_model"], m["E"], m["k"], m["d_out"]
+        label = "C5"
+    else:   # Sec. 4.4 shapes: d_model 4096, d_head 128, 16 sequences of 2048, 32 active heads, h_expert = 32 / k, E = 8k
+        k = int(args.workload.split("-k")[1])
+        B, T, d_model, E, d_out = 16, 2048, 4096, 8 * k, (32 // k) * 128
+        label = f"MoA-k{k} (Sec. 4.4 shape)"
     h, d_head = d_out // 128, 128
     N, Tk = B * T, B * T * k
     dev = torch.device("cuda:0")
@@ -235,7 +241,7 @@ def bench_momha(args):
         "value": flops / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"C5: B={B} T={T} d_model={d_model} E={E} k={k} h_expert={h} d_head={d_head}, "
+        "config": {"workload": f"{label}: B={B} T={T} d_model={d_model} E={E} k={k} h_expert={h} d_head={d_head}, "
                                "both ParallelLinears scattered->scattered, causal attention"},
         "tokens_per_s": N / (ms * 1e-3),
         "phases_ms": {"forward_with_routing": float(np.median(ts_f)), "attention_fwd": float(np.median(ts_a)),
@@ -267,7 +273,7 @@ def main():
 
     if args.sweep == "granularity":
         return granularity_sweep(args)
-    if args.workload == "C5":
+    if args.workload == "C5" or args.workload.startswith("MoA-k"):
         return bench_momha(args)
 
     import smoe_inputs as si
