@@ -11,6 +11,7 @@
 // next product takes as its B operand (no cross-lane shuffles; the matching operand is read
 // from LDS in the same permuted key order).
 #include "mfma_common.h"
+#include <type_traits>
 
 namespace {
 
@@ -65,6 +66,42 @@ __device__ __forceinline__ bf16x8 a_cols_frag(const char *tile, int c0, int s, i
   }
   return u.v;
 }
+// Per-lane byte offsets of every fragment inside a tile, worked out once: with them (and the LDS stage as a
+// compile-time constant in the unrolled loops) a fragment read is one LDS instruction whose address is a
+// register plus an immediate, instead of a dozen integer instructions per read.
+struct FragOffsets {
+  int rows[8];          // a_rows_frag(tile, ks)
+  int cols[4][2][2];    // a_cols_frag(tile, 32 * f, s), first and second transposing read
+};
+__device__ __forceinline__ FragOffsets frag_offsets(int lane) {
+  FragOffsets o;
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    int row = lane & 31;
+    o.rows[ks] = row * AROW + (((2 * ks + (lane >> 5)) ^ a_swz(row)) << 4);
+  }
+#pragma unroll
+  for (int f = 0; f < 4; ++f)
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        int col = f * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+        int row = 16 * s + 4 * (lane >> 5) + ((lane & 15) >> 2) + 8 * t;
+        o.cols[f][s][t] = row * AROW + (((col >> 3) ^ a_swz(row)) << 4) + ((col & 7) << 1);
+      }
+  return o;
+}
+__device__ __forceinline__ bf16x8 rows_frag(const char *tile, const FragOffsets &o, int ks) {
+  return *reinterpret_cast<const bf16x8 *>(tile + o.rows[ks]);
+}
+__device__ __forceinline__ bf16x8 cols_frag(const char *tile, const FragOffsets &o, int f, int s) {
+  union { bf16x8 v; s16x4 h[2]; } u;
+#pragma unroll
+  for (int t = 0; t < 2; ++t) u.h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4 *)(tile + o.cols[f][s][t]));
+  return u.v;
+}
+
 // tile row that accumulator register q of this lane belongs to (32x32 result layout)
 __device__ __forceinline__ int acc_row(int q, int lane) { return 8 * (q >> 2) + 4 * (lane >> 5) + (q & 3); }
 
@@ -132,39 +169,42 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_kernel(const bf16_t *__restri
 
   load_tile_rows(Kb, d.ldkv, 0, d.T - 1, lds0, wave, uwave, lane);
   load_tile_rows(Vb, d.ldkv, 0, d.T - 1, lds0 + ATILE, wave, uwave, lane);
-  for (int j = 0; j < n_tiles; ++j) {
+  const FragOffsets fo = frag_offsets(lane);
+  // the loop is unrolled by the two LDS stages so that every tile address below is register + constant
+  auto tile_step = [&](auto stage_c, int j) {
+    constexpr int STAGE = decltype(stage_c)::value;
     wait_loads<0>();
     __syncthreads();   // tile j has landed for everyone; everyone is done reading tile j-1
     if (j + 1 < n_tiles) {
-      uint32_t nxt = lds0 + ((j + 1) & 1) * 2 * ATILE;
+      uint32_t nxt = lds0 + (1 - STAGE) * 2 * ATILE;
       load_tile_rows(Kb, d.ldkv, (j + 1) * AKT, d.T - 1, nxt, wave, uwave, lane);
       load_tile_rows(Vb, d.ldkv, (j + 1) * AKT, d.T - 1, nxt + ATILE, wave, uwave, lane);
     }
     const int key0 = j * AKT;
-    if (key0 > wave_last) continue;   // wave-uniform: every key of the tile is in the future of all 32 rows
-    const char *kt = smem + (j & 1) * 2 * ATILE;
+    if (key0 > wave_last) return;   // wave-uniform: every key of the tile is in the future of all 32 rows
+    const char *kt = smem + STAGE * 2 * ATILE;
     const char *vt = kt + ATILE;
     f32x16 s;
 #pragma unroll
     for (int q = 0; q < 16; ++q) s[q] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_rows_frag(kt, ks, lane), qf[ks], s, 0, 0, 0);
+    for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(kt, fo, ks), qf[ks], s, 0, 0, 0);
     const bool diag = key0 + AKT - 1 > wave_first;
+    // the running maximum m stays in raw score units; the 1/sqrt(d) log2(e) factor enters the exponent's fma
     float mx = NEG_BIG;
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
-      float v = s[q] * d.scale_log2;
-      if (diag && key0 + acc_row(q, lane) > tok) v = NEG_BIG;
-      s[q] = v;
-      mx = fmaxf(mx, v);
+      if (diag && key0 + acc_row(q, lane) > tok) s[q] = NEG_BIG;
+      mx = fmaxf(mx, s[q]);
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m, mx);
-    const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+    const float alpha = __builtin_amdgcn_exp2f((m - m_new) * d.scale_log2);
+    const float shift = -m_new * d.scale_log2;
     float psum = 0.f;
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
-      float p = __builtin_amdgcn_exp2f(s[q] - m_new);
+      float p = __builtin_amdgcn_exp2f(fmaf(s[q], d.scale_log2, shift));
       s[q] = p;
       psum += p;
     }
@@ -181,9 +221,13 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_kernel(const bf16_t *__restri
     for (int f = 0; f < 4; ++f)
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2)
-        acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cols_frag(vt, f * 32, s2, lane), pb[s2], acc[f], 0, 0, 0);
+        acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(vt, fo, f, s2), pb[s2], acc[f], 0, 0, 0);
+  };
+  for (int j = 0; j < n_tiles; j += 2) {
+    tile_step(std::integral_constant<int, 0>{}, j);
+    if (j + 1 < n_tiles) tile_step(std::integral_constant<int, 1>{}, j + 1);
   }
-  // the two halves of the wavefront hold disjoint key subsets of the same query
+
   const float l_tot = l + __shfl_xor(l, 32, 64);
   const float inv = 1.0f / l_tot;
   if (row_valid) {
@@ -197,7 +241,8 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_kernel(const bf16_t *__restri
         for (int c = 0; c < 4; ++c) v[c] = (bf16_t)(acc[f][4 * g + c] * inv);
         *reinterpret_cast<bf16x4 *>(orow + f * 32 + 8 * g + 4 * (lane >> 5)) = v;
       }
-    if (lane < 32) LSE[((size_t)b * rows + r_mine) * d.h + hh] = (m + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+    if (lane < 32)
+      LSE[((size_t)b * rows + r_mine) * d.h + hh] = (m * d.scale_log2 + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
   }
 }
 
@@ -263,25 +308,28 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const bf16_t *__restri
 
   load_tile_rows(Kb, d.ldkv, 0, d.T - 1, lds0, wave, uwave, lane);
   load_tile_rows(Vb, d.ldkv, 0, d.T - 1, lds0 + ATILE, wave, uwave, lane);
-  for (int j = 0; j < n_tiles; ++j) {
+  const FragOffsets fo = frag_offsets(lane);
+  // the loop is unrolled by the two LDS stages so that every tile address below is register + constant
+  auto tile_step = [&](auto stage_c, int j) {
+    constexpr int STAGE = decltype(stage_c)::value;
     wait_loads<0>();
     __syncthreads();
     if (j + 1 < n_tiles) {
-      uint32_t nxt = lds0 + ((j + 1) & 1) * 2 * ATILE;
+      uint32_t nxt = lds0 + (1 - STAGE) * 2 * ATILE;
       load_tile_rows(Kb, d.ldkv, (j + 1) * AKT, d.T - 1, nxt, wave, uwave, lane);
       load_tile_rows(Vb, d.ldkv, (j + 1) * AKT, d.T - 1, nxt + ATILE, wave, uwave, lane);
     }
     const int key0 = j * AKT;
-    if (key0 > wave_last) continue;
-    const char *kt = smem + (j & 1) * 2 * ATILE;
+    if (key0 > wave_last) return;
+    const char *kt = smem + STAGE * 2 * ATILE;
     const char *vt = kt + ATILE;
     f32x16 s, dp;
 #pragma unroll
     for (int q = 0; q < 16; ++q) { s[q] = 0.f; dp[q] = 0.f; }
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_rows_frag(kt, ks, lane), qf[ks], s, 0, 0, 0);
+    for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(kt, fo, ks), qf[ks], s, 0, 0, 0);
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_rows_frag(vt, ks, lane), dof[ks], dp, 0, 0, 0);
+    for (int ks = 0; ks < 8; ++ks) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(vt, fo, ks), dof[ks], dp, 0, 0, 0);
     const bool diag = key0 + AKT - 1 > wave_first;
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
@@ -294,7 +342,11 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const bf16_t *__restri
     for (int f = 0; f < 4; ++f)
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2)
-        acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cols_frag(kt, f * 32, s2, lane), db[s2], acc[f], 0, 0, 0);
+        acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(kt, fo, f, s2), db[s2], acc[f], 0, 0, 0);
+  };
+  for (int j = 0; j < n_tiles; j += 2) {
+    tile_step(std::integral_constant<int, 0>{}, j);
+    if (j + 1 < n_tiles) tile_step(std::integral_constant<int, 1>{}, j + 1);
   }
   if (row_valid) {
     bf16_t *orow = dQ + qrow;
@@ -384,30 +436,33 @@ __global__ void __launch_bounds__(64 * NW, 2) attn_bwd_dkv_kernel(const bf16_t *
   load_tile_rows<NW>(Qb, d.ldq, t_first * AKT, rows - 1, lds0, wave, uwave, lane);
   load_tile_rows<NW>(dOb, d.ldq, t_first * AKT, rows - 1, lds0 + ATILE, wave, uwave, lane);
   load_stats(t_first, 0);
-  for (int j = 0; j < n_tiles; ++j) {
+  const FragOffsets fo = frag_offsets(lane);
+  // the loop is unrolled by the two LDS stages so that every tile address below is register + constant
+  auto tile_step = [&](auto stage_c, int j) {
+    constexpr int STAGE = decltype(stage_c)::value;
     wait_loads<0>();
     __syncthreads();
     const int tile = t_first + j;
     if (j + 1 < n_tiles) {
-      uint32_t nxt = lds0 + ((j + 1) & 1) * 2 * ATILE;
+      uint32_t nxt = lds0 + (1 - STAGE) * 2 * ATILE;
       load_tile_rows<NW>(Qb, d.ldq, (tile + 1) * AKT, rows - 1, nxt, wave, uwave, lane);
       load_tile_rows<NW>(dOb, d.ldq, (tile + 1) * AKT, rows - 1, nxt + ATILE, wave, uwave, lane);
       load_stats(tile + 1, (j + 1) & 1);
     }
     const int r0 = tile * AKT;
     const int tile_last_tok = min(r0 + AKT - 1, rows - 1) / d.G;
-    if (tile_last_tok < wave_key0) continue;                    // none of these rows sees any key of this wavefront
-    const char *qt = smem + (j & 1) * 2 * ATILE;
+    if (tile_last_tok < wave_key0) return;                    // none of these rows sees any key of this wavefront
+    const char *qt = smem + STAGE * 2 * ATILE;
     const char *dot = qt + ATILE;
     f32x16 s, dp;
 #pragma unroll
     for (int q = 0; q < 16; ++q) { s[q] = 0.f; dp[q] = 0.f; }
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_rows_frag(qt, ks, lane), kf[ks], s, 0, 0, 0);
+    for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(qt, fo, ks), kf[ks], s, 0, 0, 0);
     if (DK) {
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks)
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_rows_frag(dot, ks, lane), a_rows_frag(vmine, ks, lane), dp, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(dot, fo, ks), rows_frag(vmine, fo, ks), dp, 0, 0, 0);
     }
     // rows of this tile that are earlier than the wavefront's last key, or past the end, need the mask
     const bool edge = (r0 / d.G < wave_key0 + 31) || (r0 + AKT > rows);
@@ -436,9 +491,13 @@ __global__ void __launch_bounds__(64 * NW, 2) attn_bwd_dkv_kernel(const bf16_t *
     for (int f = 0; f < 4; ++f)
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
-        if (DV) accv[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cols_frag(dot, f * 32, s2, lane), pb[s2], accv[f], 0, 0, 0);
-        if (DK) acck[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_cols_frag(qt, f * 32, s2, lane), db[s2], acck[f], 0, 0, 0);
+        if (DV) accv[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(dot, fo, f, s2), pb[s2], accv[f], 0, 0, 0);
+        if (DK) acck[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(qt, fo, f, s2), db[s2], acck[f], 0, 0, 0);
       }
+  };
+  for (int j = 0; j < n_tiles; j += 2) {
+    tile_step(std::integral_constant<int, 0>{}, j);
+    if (j + 1 < n_tiles) tile_step(std::integral_constant<int, 1>{}, j + 1);
   }
   if (nch > 1) {   // partial sums of this chunk: [unit][dK | dV][key][128] fp32
     float *pk = part + ((((size_t)b * d.h + hh) * plan.units + blockIdx.x) * 2) * (32 * NW) * AD +
