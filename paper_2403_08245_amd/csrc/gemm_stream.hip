@@ -218,7 +218,10 @@ template <bool TRANS_W> struct S2SStreamOps {
   }
 };
 
-template <bool TRANS_W, bool SCATTER_OUT, int ACT = 0>   // ACT 1: fused SwiGLU keeping the pre-activation, 2: without
+// ACT 1: fused SwiGLU keeping the pre-activation, 2: without.  STATIC4: the contraction is a multiple of four
+// half-steps, so every tile starts in LDS stage 0 and the loop is written out four slots at a time with the
+// stage as a compile-time constant: all LDS addresses become a loop-invariant register plus an immediate.
+template <bool TRANS_W, bool SCATTER_OUT, int ACT = 0, bool STATIC4 = false>
 __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int tiles_n, int group_m, int total_vids,
                                                                  uint32_t magic_a) {
   static_assert(ACT == 0 || (!TRANS_W && !SCATTER_OUT), "the fused activation belongs to the forward, sorted-output product");
@@ -368,12 +371,42 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
     advance_loader();
     ++g;
   };
+  auto static_slot = [&](auto first, auto stage) {
+    constexpr int S = decltype(stage)::value;
+    half_step<decltype(first)::value>(ops, smem + S * STAGE_BYTES, smem + ((S + 1) & 3) * STAGE_BYTES,
+                                      lds0 + ((S + 3) & 3) * STAGE_BYTES, wm, wn, lane, fa, fb, acc);
+    advance_loader();
+  };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  using I3 = std::integral_constant<int, 3>;
   open_slot();
   for (;;) {   // one tile per trip; its first slot has been opened already
-    one_slot(std::true_type{});
-    for (int h = 1; h < nh; ++h) {
+    if (STATIC4) {
+      static_slot(std::true_type{}, I0{});
       open_slot();
-      one_slot(std::false_type{});
+      static_slot(std::false_type{}, I1{});
+      open_slot();
+      static_slot(std::false_type{}, I2{});
+      open_slot();
+      static_slot(std::false_type{}, I3{});
+      for (int h = 4; h < nh; h += 4) {
+        open_slot();
+        static_slot(std::false_type{}, I0{});
+        open_slot();
+        static_slot(std::false_type{}, I1{});
+        open_slot();
+        static_slot(std::false_type{}, I2{});
+        open_slot();
+        static_slot(std::false_type{}, I3{});
+      }
+    } else {
+      one_slot(std::true_type{});
+      for (int h = 1; h < nh; ++h) {
+        open_slot();
+        one_slot(std::false_type{});
+      }
     }
     // The next tile's first slot is opened before the epilogue: stores share the load counter,
     // so this wait would otherwise also sit out the acknowledgement of every store below.
@@ -589,15 +622,20 @@ template <typename K> int set_lds_limit(K kernel, int bytes) {
 
 uint32_t division_magic(int fan) { return fan > 1 ? (uint32_t)((0x100000000ULL + fan - 1) / fan) : 0u; }
 
+template <bool TRANS_W, bool SCATTER_OUT, int ACT = 0, bool STATIC4 = false> int launch_s2s_stream_one(hipStream_t s, const S2SArgs &a);
 template <bool TRANS_W, bool SCATTER_OUT, int ACT = 0> int launch_s2s_stream_cfg(hipStream_t s, const S2SArgs &a) {
-  static int attr_rc = set_lds_limit(s2s_stream_kernel<TRANS_W, SCATTER_OUT, ACT>, STREAM_LDS_BYTES);
+  return a.K % (4 * HK) == 0 ? launch_s2s_stream_one<TRANS_W, SCATTER_OUT, ACT, true>(s, a)
+                             : launch_s2s_stream_one<TRANS_W, SCATTER_OUT, ACT, false>(s, a);
+}
+template <bool TRANS_W, bool SCATTER_OUT, int ACT, bool STATIC4> int launch_s2s_stream_one(hipStream_t s, const S2SArgs &a) {
+  static int attr_rc = set_lds_limit(s2s_stream_kernel<TRANS_W, SCATTER_OUT, ACT, STATIC4>, STREAM_LDS_BYTES);
   if (attr_rc != SMOE_OK) return attr_rc;
   int tiles_n = ACT ? ceil_div(a.N / 2, TB / 2) : ceil_div(a.N, TB);
   int tiles_m = ceil_div(a.Tk, TB) + a.E;     // upper bound on sum_e ceil(n_e / 256)
   int group_m = 4;
   long long total = (long long)ceil_div(tiles_m, group_m) * group_m * tiles_n;
   if (total > 0x7fffffffLL) return SMOE_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL((s2s_stream_kernel<TRANS_W, SCATTER_OUT, ACT>), dim3(STREAM_GRID), dim3(NTHREADS), STREAM_LDS_BYTES, s, a, tiles_n,
+  hipLaunchKernelGGL((s2s_stream_kernel<TRANS_W, SCATTER_OUT, ACT, STATIC4>), dim3(STREAM_GRID), dim3(NTHREADS), STREAM_LDS_BYTES, s, a, tiles_n,
                      group_m, (int)total, division_magic(a.a_map.o ? a.a_map.fan : 1));
   SMOE_LAUNCH_CHECK();
   return SMOE_OK;
