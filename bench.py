@@ -364,7 +364,7 @@ def main():
     esz = 2 if cfg.dtype == "bf16" else 4
     s2s_bytes = float(esz) * (int((rows > 0).sum()) * cfg.d_model * d_h + cfg.Tk * cfg.d_model + cfg.Tk * d_h)
     t_mfma, t_hbm = s2s_flops / (peak * 1e12), s2s_bytes / (PEAK_HBM_GBS * 1e9)
-    kname = "s2s_stream_kernel<false,false,0> (ParallelLinear #1, scattered->grouped)"
+    kname = "s2s_stream_kernel<false,false,0,true> (ParallelLinear #1, scattered->grouped)"
     if t_hbm > t_mfma:
         gbs = s2s_bytes / (ms_s2s * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": kname, "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
