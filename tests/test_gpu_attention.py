@@ -166,3 +166,40 @@ def test_attention_C5_size_sampled_heads(smoe):
         other = dK.clone()
         other[b, :, hh] = 0
         assert other.abs().max().item() == 0          # no other head or sequence received a gradient
+
+
+def test_attention_error_codes(smoe):
+    import ctypes
+    lib, ctx = smoe.lib, smoe.ctx()
+    B, T, G, h = 1, 8, 2, 1
+    Q = torch.zeros(B, T, G, h, 128, dtype=torch.bfloat16, device="cuda")
+    K = torch.zeros(B, T, h, 128, dtype=torch.bfloat16, device="cuda")
+    L = torch.zeros(B, T, G, h, dtype=torch.float32, device="cuda")
+    p = lambda t: ctypes.c_void_p(t.data_ptr())
+    # head widths other than 128 and fp32 are valid requests this build has no kernel for
+    assert lib.smoe_attention_fwd(ctx, None, smoe.BF16, p(Q), p(K), p(K), B, T, G, h, 64, p(Q), p(L)) == -2
+    assert lib.smoe_attention_fwd(ctx, None, smoe.F32, p(Q), p(K), p(K), B, T, G, h, 128, p(Q), p(L)) == -2
+    assert lib.smoe_attention_fwd(ctx, None, smoe.BF16, None, p(K), p(K), B, T, G, h, 128, p(Q), p(L)) == -1
+    assert lib.smoe_attention_fwd(ctx, None, smoe.BF16, p(Q), p(K), p(K), B, 0, G, h, 128, p(Q), p(L)) == -1
+    need = lib.smoe_attention_bwd_workspace_bytes(B, T, G, h)
+    assert need >= B * T * G * h * 4
+    ws = torch.empty(256, dtype=torch.uint8, device="cuda")
+    rc = lib.smoe_attention_bwd(ctx, None, smoe.BF16, p(Q), p(Q), p(K), p(K), p(Q), p(L), B, T, G, h, 128, p(Q), p(K), p(K),
+                                p(ws), 16)
+    assert rc == -3            # workspace too small
+    with pytest.raises(smoe.SmoeError):
+        smoe.attention_fwd(torch.zeros(1, 4, 1, 1, 64, dtype=torch.bfloat16, device="cuda"),
+                           torch.zeros(1, 4, 1, 64, dtype=torch.bfloat16, device="cuda"),
+                           torch.zeros(1, 4, 1, 64, dtype=torch.bfloat16, device="cuda"))
+
+
+def test_attention_is_deterministic(smoe):
+    B, T, G, h = 2, 200, 3, 2
+    Q, K, V, dO = (_bf16(s, i).cuda() for i, s in enumerate([(B, T, G, h, 128), (B, T, h, 128), (B, T, h, 128), (B, T, G, h, 128)]))
+    O1, L1 = smoe.attention_fwd(Q, K, V)
+    g1 = smoe.attention_bwd(dO, Q, K, V, O1, L1)
+    O2, L2 = smoe.attention_fwd(Q, K, V)
+    g2 = smoe.attention_bwd(dO, Q, K, V, O2, L2)
+    assert torch.equal(O1, O2) and torch.equal(L1, L2)
+    for a, b in zip(g1, g2):
+        assert torch.equal(a, b)
