@@ -228,6 +228,19 @@ def test_mlp_ragged_shapes_with_empty_experts(smoe, act, dtype):
     _mlp_parity(smoe, cfg, 4)
 
 
+@pytest.mark.parametrize("d_model,d_expert", [(160, 200), (384, 72), (128, 136)])
+def test_mlp_fused_swiglu_ragged_widths(smoe, d_model, d_expert):
+    """bf16 SwiGLU through the persistent kernels (activation in the first product's epilogue) with hidden
+    widths that leave the last gate/up tile partly empty, contractions that are and are not a multiple of
+    128, training and inference."""
+    cfg = si.custom(f"fused{d_model}x{d_expert}", T=301, d_model=d_model, d_expert=d_expert, E=5, k=2, act=si.ACT_SWIGLU,
+                    dtype="bf16")
+    case, (X, W1, W2, dYc, r, gg) = _mlp_parity(smoe, cfg, 11)
+    Yt, _ = smoe.mlp_fwd(X, W1, W2, r, cfg.k, gg, cfg.act, training=True)
+    Yi, _ = smoe.mlp_fwd(X, W1, W2, r, cfg.k, gg, cfg.act, training=False)
+    assert torch.equal(Yt, Yi)
+
+
 def test_mlp_k1_and_k_equals_E(smoe):
     _mlp_parity(smoe, si.custom("k1", T=130, d_model=64, d_expert=64, E=4, k=1, act=si.ACT_SWIGLU, dtype="bf16"), 5)
     _mlp_parity(smoe, si.custom("kE", T=50, d_model=64, d_expert=32, E=4, k=4, act=si.ACT_GELU, dtype="f32"), 6)
