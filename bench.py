@@ -114,7 +114,8 @@ def granularity_sweep(args):
         torch.cuda.empty_cache()
         return out
 
-    dense = run(si.CONFIGS["G-dense"])
+    sparsity = args.sweep == "sparsity"
+    dense = run(si.CONFIGS["S-dense" if sparsity else "G-dense"])
 
     def vendor_dense():
         """The same dense MLP with the vendor's GEMM (torch.matmul) and torch's GELU, for context only."""
@@ -155,15 +156,26 @@ def granularity_sweep(args):
             out[name] = {"ms_median": float(np.median(ts)), "tflops": flops / (np.median(ts) * 1e-3) / 1e12}
         return out
 
-    vendor = vendor_dense()
+    vendor = None if sparsity else vendor_dense()
     torch.cuda.empty_cache()
     rows = []
-    for k in si.GRANULARITY_KS:
-        cfg = si.CONFIGS[f"G{k}"]
+    for k in (si.SPARSITY_KS if sparsity else si.GRANULARITY_KS):
+        cfg = si.CONFIGS[f"S{k}" if sparsity else f"G{k}"]
         res = run(cfg)
         rows.append({"k": k, "E": cfg.E, "d_expert": cfg.d_expert, **res,
                      "relative_throughput_training": dense["training"]["ms_median"] / res["training"]["ms_median"],
                      "relative_throughput_inference": dense["inference"]["ms_median"] / res["inference"]["ms_median"]})
+    if sparsity:
+        head = next(r for r in rows if r["k"] == 8)
+        print(json.dumps({
+            "metric": "SMoE MLP fwd+bwd GEMM throughput per layer, E=64 k=8 d_expert=1024 (Sec. 4.3 sweep)",
+            "value": head["training"]["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": head["training"]["ms_median"], "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "sparsity sweep: T=61440 d_model=4096 E=64 d_expert=1024 act=gelu, uniform router, "
+                                   "k in (1,2,4,8,16,30); dense = one expert of 65536 hidden units"},
+            "dense_all_parameters": dense, "sweep": rows}))
+        return
     head = next(r for r in rows if r["k"] == 4)
     print(json.dumps({
         "metric": "SMoE MLP fwd+bwd GEMM throughput per layer, unit-benchmark shape E=32 k=4 (Sec. 4.1)",
@@ -263,15 +275,16 @@ def main():
     ap.add_argument("--kernel-reps", type=int, default=20)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB elementwise copy kernel (reference for the HBM byte counters)")
-    ap.add_argument("--sweep", choices=["granularity"], default=None,
-                    help="run the Sec. 4.2 granularity sweep instead of one workload (one JSON line with all points)")
+    ap.add_argument("--sweep", choices=["granularity", "sparsity"], default=None,
+                    help="run the Sec. 4.2 granularity sweep or the Sec. 4.3 sparsity sweep instead of one workload "
+                         "(one JSON line with all points)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (data-parallel sharding is a design note); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
 
-    if args.sweep == "granularity":
+    if args.sweep:
         return granularity_sweep(args)
     if args.workload == "C5" or args.workload.startswith("MoA-k"):
         return bench_momha(args)

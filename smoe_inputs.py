@@ -68,6 +68,12 @@ GRANULARITY_KS = (1, 2, 4, 8, 16)
 for _k in GRANULARITY_KS:
     CONFIGS[f"G{_k}"] = MLPConfig(f"G{_k}", 30 * 2048, 4096, 8192 // _k, 8 * _k, _k, ACT_GELU)
 CONFIGS["G-dense"] = MLPConfig("G-dense", 30 * 2048, 4096, 8192, 1, 1, ACT_GELU)
+# Decreasing sparsity, Sec. 4.3: E = 64 experts of the unit benchmark's width at E = 64 (d_expert = 1024), k growing
+# to 30; "S-dense" is the fully dense MLP holding all E * d_expert hidden units.
+SPARSITY_KS = (1, 2, 4, 8, 16, 30)
+for _k in SPARSITY_KS:
+    CONFIGS[f"S{_k}"] = MLPConfig(f"S{_k}", 30 * 2048, 4096, 1024, 64, _k, ACT_GELU)
+CONFIGS["S-dense"] = MLPConfig("S-dense", 30 * 2048, 4096, 64 * 1024, 1, 1, ACT_GELU)
 
 # Mixture-of-Attention projections (Alg. 4): W_Q [E,d_model,d_out], W_O [E,d_out,d_model]
 MOA_C5 = dict(T=8192, d_model=2048, E=16, k=4, d_out=512)
