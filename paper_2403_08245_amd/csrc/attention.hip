@@ -102,6 +102,11 @@ __device__ __forceinline__ bf16x8 cols_frag(const char *tile, const FragOffsets 
   return u.v;
 }
 
+// Makes a value loaded from global memory "arrive" here: the compiler waits for the load at this point and
+// not at the value's first use inside a loop, where its counted wait would also sit out the direct-to-LDS
+// loads that were just issued for the next tile (the hardware counter does not tell them apart).
+template <typename T> __device__ __forceinline__ void settle(T &v) { __asm__ volatile("" : "+v"(v)); }
+
 // tile row that accumulator register q of this lane belongs to (32x32 result layout)
 __device__ __forceinline__ int acc_row(int q, int lane) { return 8 * (q >> 2) + 4 * (lane >> 5) + (q & 3); }
 
@@ -158,6 +163,8 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_kernel(const bf16_t *__restri
   bf16x8 qf[8];
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(Q + qrow + 16 * ks + 8 * (lane >> 5));
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) settle(qf[ks]);
 
   const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
   f32x16 acc[4];
@@ -192,11 +199,13 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_kernel(const bf16_t *__restri
     const bool diag = key0 + AKT - 1 > wave_first;
     // the running maximum m stays in raw score units; the 1/sqrt(d) log2(e) factor enters the exponent's fma
     float mx = NEG_BIG;
+    if (diag) {   // wave-uniform: only tiles that straddle the diagonal pay for the mask
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
-      if (diag && key0 + acc_row(q, lane) > tok) s[q] = NEG_BIG;
-      mx = fmaxf(mx, s[q]);
+      for (int q = 0; q < 16; ++q)
+        if (key0 + acc_row(q, lane) > tok) s[q] = NEG_BIG;
     }
+#pragma unroll
+    for (int q = 0; q < 16; ++q) mx = fmaxf(mx, s[q]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m, mx);
     const float alpha = __builtin_amdgcn_exp2f((m - m_new) * d.scale_log2);
@@ -295,9 +304,13 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const bf16_t *__restri
     dof[ks] = *reinterpret_cast<const bf16x8 *>(dO + qrow + 16 * ks + 8 * (lane >> 5));
   }
   const size_t stat = ((size_t)b * rows + r_mine) * d.h + hh;
-  const float lse2 = LSE[stat] * 1.4426950408889634f;
-  const float dlt = delta[stat];
+  float lse2 = LSE[stat] * 1.4426950408889634f;
+  float dlt = delta[stat];
   const float scale = d.scale_log2 * 0.6931471805599453f;
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) { settle(qf[ks]); settle(dof[ks]); }
+  settle(lse2);
+  settle(dlt);
 
   const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_address(smem));
   f32x16 acc[4];
@@ -331,10 +344,14 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const bf16_t *__restri
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rows_frag(vt, fo, ks), dof[ks], dp, 0, 0, 0);
     const bool diag = key0 + AKT - 1 > wave_first;
+    if (diag) {
+#pragma unroll
+      for (int q = 0; q < 16; ++q)
+        if (key0 + acc_row(q, lane) > tok) s[q] = NEG_BIG;   // exp2 of it is 0
+    }
 #pragma unroll
     for (int q = 0; q < 16; ++q) {
-      float p = __builtin_amdgcn_exp2f(s[q] * d.scale_log2 - lse2);
-      if (diag && key0 + acc_row(q, lane) > tok) p = 0.f;
+      float p = __builtin_amdgcn_exp2f(fmaf(s[q], d.scale_log2, -lse2));
       s[q] = p * (dp[q] - dlt) * scale;
     }
     bf16x8 db[2] = {pack8(s, 0), pack8(s, 1)};
@@ -403,6 +420,8 @@ __global__ void __launch_bounds__(64 * NW, 2) attn_bwd_dkv_kernel(const bf16_t *
   bf16x8 kf[8];
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) kf[ks] = *reinterpret_cast<const bf16x8 *>(K + krow + 16 * ks + 8 * (lane >> 5));
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) settle(kf[ks]);
   const char *vmine = s_v + wave * ATILE;
   load_tile_rows<1>(V + (size_t)b * d.T * d.ldkv + hh * AD, d.ldkv, wave_key0, d.T - 1,
                     __builtin_amdgcn_readfirstlane(lds_address(s_v)) + uwave * ATILE, 0, 0, lane);
