@@ -433,8 +433,9 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
 // `group` copy followed by this kernel, the same ranking the paper reports).
 // ======================================================================================
 // The loader cursor runs three slots ahead of the multiplying cursor over the same slot
-// sequence: max(half-steps, 1) slots per tile, tiles in largest-expert-first order.  A tile of
-// an empty expert has one idle slot and writes zeros.
+// sequence: the half-steps of a tile rounded up to a multiple of four (at least four) slots,
+// tiles in largest-expert-first order.  Slots past a segment's end load a block of zeros, so a
+// tile of an empty expert multiplies zeros and writes zeros.
 struct DWCursor {
   int seq;        // position in this block's tile list
   int step, ns;   // slot within the tile, slots of the tile
@@ -510,7 +511,10 @@ __global__ void __launch_bounds__(NTHREADS, 1) dw_stream_kernel(DWArgs a, int ti
     c.m0 = (band * group_m + r % group_m) * TB;
     c.n0 = (r / group_m) * TB;
     c.nh = (c.hi - c.lo + HK - 1) / HK;
-    c.ns = max(c.nh, 1);
+    // Slots come in groups of four so that every tile starts in LDS stage 0 and the loop can be written
+    // with compile-time stages; the up to three extra slots (four for an empty expert) load the zero
+    // block and add nothing.
+    c.ns = max((c.nh + 3) & ~3, 4);
     c.step = 0;
   };
   auto advance = [&](DWCursor &c) {
@@ -558,50 +562,39 @@ __global__ void __launch_bounds__(NTHREADS, 1) dw_stream_kernel(DWArgs a, int ti
 #pragma unroll
   for (int j = 0; j < FR; ++j) fb[0][j] = ops.frag_b(smem + TILE_BYTES, wn * (TB / 2) + j * 32, 0, lane);
 
-  int g = 0;
   auto open_slot = [&]() {
     wait_loads<2 * NLD>();
     __syncthreads();
   };
-  auto one_slot = [&](auto first) {
-    const char *cur = smem + (g & 3) * STAGE_BYTES;
-    const char *nxt = smem + ((g + 1) & 3) * STAGE_BYTES;
-    const uint32_t fill = lds0 + ((g + 3) & 3) * STAGE_BYTES;
+  auto static_slot = [&](auto first, auto stage) {
+    constexpr int S = decltype(stage)::value;
     resolve(lc);
-    half_step<decltype(first)::value>(ops, cur, nxt, fill, wm, wn, lane, fa, fb, acc);
+    half_step<decltype(first)::value>(ops, smem + S * STAGE_BYTES, smem + ((S + 1) & 3) * STAGE_BYTES,
+                                      lds0 + ((S + 3) & 3) * STAGE_BYTES, wm, wn, lane, fa, fb, acc);
     advance(lc);
-    ++g;
   };
-  auto idle_slot = [&]() {   // tile of an empty expert: keep the loader and the load count going, result is zero
-    const uint32_t fill = lds0 + ((g + 3) & 3) * STAGE_BYTES;
-    const char *nxt = smem + ((g + 1) & 3) * STAGE_BYTES;
-    resolve(lc);
-#pragma unroll
-    for (int I = 0; I < 2 * NLD; ++I) ops.load(I, fill + (I / NLD) * TILE_BYTES);
-    advance(lc);
-#pragma unroll
-    for (int i = 0; i < FR; ++i)
-#pragma unroll
-      for (int j = 0; j < FR; ++j)
-#pragma unroll
-        for (int q = 0; q < 16; ++q) acc[i][j][q] = 0.f;
-    // the fragments of the next slot were not prefetched by a multiplying slot: read them here
-#pragma unroll
-    for (int i = 0; i < FR; ++i) fa[0][i] = ops.frag_a(nxt, wm * (TB / 2) + i * 32, 0, lane);
-#pragma unroll
-    for (int j = 0; j < FR; ++j) fb[0][j] = ops.frag_b(nxt + TILE_BYTES, wn * (TB / 2) + j * 32, 0, lane);
-    ++g;
-  };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  using I3 = std::integral_constant<int, 3>;
   open_slot();
   for (;;) {   // one tile per trip; its first slot has been opened already
-    if (cc.nh > 0) {
-      one_slot(std::true_type{});
-      for (int h = 1; h < cc.nh; ++h) {
-        open_slot();
-        one_slot(std::false_type{});
-      }
-    } else {
-      idle_slot();
+    static_slot(std::true_type{}, I0{});
+    open_slot();
+    static_slot(std::false_type{}, I1{});
+    open_slot();
+    static_slot(std::false_type{}, I2{});
+    open_slot();
+    static_slot(std::false_type{}, I3{});
+    for (int h = 4; h < cc.ns; h += 4) {
+      open_slot();
+      static_slot(std::false_type{}, I0{});
+      open_slot();
+      static_slot(std::false_type{}, I1{});
+      open_slot();
+      static_slot(std::false_type{}, I2{});
+      open_slot();
+      static_slot(std::false_type{}, I3{});
     }
     open_slot();   // the next tile's first slot, before the stores below join the load counter
     const int mbase = cc.m0 + wm * (TB / 2);
