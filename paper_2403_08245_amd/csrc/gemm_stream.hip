@@ -445,28 +445,20 @@ struct DWCursor {
 };
 
 struct DWStreamOps {
-  const bf16_t *A, *B;
-  int M, N;
   int ra[NLD], ka[NLD];      // per load instruction: contraction row within a slot, 16-byte column chunk
   int uwave;
-  // the loader's current slot (uniform)
-  int row_base, row_end, m0, n0;
-  bool real;
-  // Source address of load instruction I for the current slot; rows past the segment and idle
-  // slots read a block of zeros so they add nothing to the sum.
-  __device__ __forceinline__ const bf16_t *prepare(int I) const {
-    const int J = I % NLD;
-    const bool is_a = I < NLD;
-    int i = row_base + ra[J];
-    int col = (is_a ? m0 : n0) + ka[J] * 8;
-    if (col >= (is_a ? M : N)) col = 0;
-    const bf16_t *p = (is_a ? A : B) + (size_t)i * (is_a ? M : N) + col;
-    return (real && i < row_end) ? p : (const bf16_t *)g_zero16;
+  // The loader's current group of four slots: range-checked windows that start at the group's first
+  // row and end with the expert's segment (rows past it, padded slots and empty experts read zeros and
+  // add nothing to the sum), per-lane byte offsets of the tile's columns inside a slot, and the byte
+  // offset of the current slot inside the group.
+  int32x4 win_a, win_b;
+  uint32_t oa[NLD], ob[NLD];
+  uint32_t sub_a, sub_b;
+  __device__ __forceinline__ uint32_t prepare(int I) const { return I < NLD ? oa[I] + sub_a : ob[I - NLD] + sub_b; }
+  __device__ __forceinline__ void issue(int I, uint32_t off, uint32_t lds) const {
+    load16_to_lds_checked(I < NLD ? win_a : win_b, off, lds);
   }
-  __device__ __forceinline__ void issue(int, const bf16_t *src, uint32_t lds) const { load16_to_lds(src, lds); }
-  __device__ __forceinline__ void load(int I, uint32_t tile_lds) {
-    load16_to_lds(prepare(I), tile_lds + inst_off(uwave, I % NLD));
-  }
+  __device__ __forceinline__ void load(int I, uint32_t tile_lds) { issue(I, prepare(I), tile_lds + inst_off(uwave, I % NLD)); }
   __device__ __forceinline__ bf16x8 frag_a(const char *tile, int base, int kk, int l) { return tr_frag(tile, base, kk, l); }
   __device__ __forceinline__ bf16x8 frag_b(const char *tile, int base, int kk, int l) { return tr_frag(tile, base, kk, l); }
 };
@@ -520,24 +512,41 @@ __global__ void __launch_bounds__(NTHREADS, 1) dw_stream_kernel(DWArgs a, int ti
   auto advance = [&](DWCursor &c) {
     if (!c.live) return;
     if (++c.step < c.ns) return;
+    // keeps the tile lookup behind this (rarely taken) branch: without it the compiler evaluates
+    // the lookup's integer divisions in every half-step and selects the results
+    __asm__ volatile("" ::: "memory");
     open_tile(c, c.seq + 1);
   };
 
   DWStreamOps ops;
   ops.uwave = __builtin_amdgcn_readfirstlane(wave);
-  ops.A = (const bf16_t *)a.A;
-  ops.B = (const bf16_t *)a.B;
-  ops.M = a.M;
-  ops.N = a.N;
 #pragma unroll
   for (int I = 0; I < NLD; ++I) tr_lane_slot(wave, lane, I, ops.ra[I], ops.ka[I]);
+  const bf16_t *A = (const bf16_t *)a.A, *B = (const bf16_t *)a.B;
+  const uint32_t row_a = (uint32_t)a.M * 2u, row_b = (uint32_t)a.N * 2u;   // bytes per operand row
   // loader cursor: publish the slot whose eight loads are issued next
+  int shown_m0 = -1, shown_n0 = -1;
   auto resolve = [&](const DWCursor &c) {
-    ops.real = c.live && c.nh > 0;
-    ops.row_base = c.lo + c.step * HK;
-    ops.row_end = c.hi;
-    ops.m0 = c.m0;
-    ops.n0 = c.n0;
+    const int first = c.lo + (c.step & ~3) * HK;                 // first row of this group of four slots
+    const int left = c.live ? max(c.hi - first, 0) : 0;          // rows of the segment from there on
+    const int base_row = left > 0 ? first : 0;
+    const unsigned long long cap = 0xffffffffull;
+    ops.win_a = buffer_window(A + (size_t)base_row * a.M, (uint32_t)min((unsigned long long)left * row_a, cap));
+    ops.win_b = buffer_window(B + (size_t)base_row * a.N, (uint32_t)min((unsigned long long)left * row_b, cap));
+    ops.sub_a = (uint32_t)(c.step & 3) * HK * row_a;
+    ops.sub_b = (uint32_t)(c.step & 3) * HK * row_b;
+    if (c.m0 != shown_m0 || c.n0 != shown_n0) {                  // a new tile: its columns' offsets inside a slot
+      shown_m0 = c.m0;
+      shown_n0 = c.n0;
+#pragma unroll
+      for (int J = 0; J < NLD; ++J) {
+        int ca = c.m0 + ops.ka[J] * 8, cb = c.n0 + ops.ka[J] * 8;
+        if (ca >= a.M) ca = 0;
+        if (cb >= a.N) cb = 0;
+        ops.oa[J] = (uint32_t)ops.ra[J] * row_a + (uint32_t)ca * 2u;
+        ops.ob[J] = (uint32_t)ops.ra[J] * row_b + (uint32_t)cb * 2u;
+      }
+    }
   };
 
   DWCursor cc, lc;

@@ -36,6 +36,23 @@ __device__ __forceinline__ void load16_to_lds(const void *base, uint32_t byte_of
   __asm__ volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(byte_off), "s"(base)
                    : "memory", "m0");
 }
+// Range-checked form: a raw buffer descriptor (base address, byte count) in four scalar registers and a
+// 32-bit lane offset; a lane whose bytes lie past the byte count lands zeros in LDS instead of loading.
+// Used where rows past the end of a segment have to contribute nothing to a sum.
+typedef int int32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ int32x4 buffer_window(const void *base, uint32_t bytes) {
+  const unsigned long long p = (unsigned long long)base;
+  int32x4 r;
+  r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)p);
+  r[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)((p >> 32) & 0xffffu));   // stride 0: a raw buffer
+  r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+  r[3] = 0x00020000;                                                            // 32-bit raw data format
+  return r;
+}
+__device__ __forceinline__ void load16_to_lds_checked(int32x4 window, uint32_t byte_off, uint32_t lds_addr) {
+  __asm__ volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds_addr), "v"(byte_off), "s"(window)
+                   : "memory", "m0");
+}
 __device__ __forceinline__ void load4_to_lds(const void *gsrc, uint32_t lds_addr) {
   __asm__ volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_addr), "v"(gsrc) : "memory", "m0");
 }
