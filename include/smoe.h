@@ -116,7 +116,8 @@ int smoe_route(smoe_ctx *ctx, void *stream, const int32_t *expert_idxs, int T, i
  *         grouped_out must be 0 and Y [Tk / gates_k, d_out] (out) receives
  *         Y[t] = sum_j gates[t*kp+j] * Yhat[t*kp+j]   (Alg. 1's view + bmm).
  *         gates = NULL: Y must be NULL and Yhat is the result.
- * No workspace is needed. */
+ * No workspace is needed (so this entry point always runs whole output tiles; the calls that
+ * take a workspace also keep 64 MiB of it for the split last round described there). */
 int smoe_plinear_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *X, int x_rows,
                      int d_in, const void *W, int d_out, const smoe_routing *r, int k,
                      const float *gates, int gates_k, int grouped_in, int grouped_out,
@@ -132,7 +133,10 @@ int smoe_plinear_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *
  * Either of dX / dW may be NULL to skip it.  Steps as in Alg. 2: dgates row dots, `group` of
  * dY (weighted by the gates) and of X whenever they are not already expert-sorted, groupXTY
  * for dW on the two grouped operands, scatter2scatter with W^T for dX, and the sum over a
- * row's k slots when the input was scattered.  The workspace holds the grouped copies. */
+ * row's k slots when the input was scattered.  The workspace holds the grouped copies and
+ * 64 MiB for fp32 partial output tiles: when the output tiles of a product do not fill a last
+ * round of the persistent grid, that round's contraction is cut into up to four chunks run
+ * by otherwise idle blocks, and a second kernel adds the chunks in a fixed order. */
 size_t smoe_plinear_bwd_workspace_bytes(smoe_dtype dtype, int x_rows, int d_in, int d_out, int Tk,
                                         int k, int has_gates, int grouped_in, int grouped_out);
 int smoe_plinear_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *dY, const void *X,
@@ -148,7 +152,9 @@ int smoe_plinear_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *
  *   W2 [E, d_expert, d_model];  gates [T*k] fp32;  Y [T, d_model] (out).
  *   saved_Hpre [Tk, d_h], saved_H [Tk, d_expert] (expert-sorted order) and saved_Yhat
  *   [Tk, d_model] (slot order): outputs kept for the backward pass.  Pass all three or
- *   none; with none (inference) the workspace holds them instead. */
+ *   none; with none (inference) the workspace holds them instead.  In both modes the
+ *   workspace also holds the 64 MiB of partial tiles of a split last round (see
+ *   smoe_plinear_bwd), so it is never empty. */
 size_t smoe_mlp_fwd_workspace_bytes(smoe_dtype dtype, smoe_act act, int T, int k, int d_model,
                                     int d_expert, int training);
 int smoe_mlp_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, const void *X, int T,

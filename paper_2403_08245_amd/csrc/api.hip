@@ -40,6 +40,7 @@ S2SArgs make_s2s(const void *A, const void *W, void *C, const smoe_routing *r, i
   a.w_stride = (size_t)d_in * d_out;
   a.trans_w = trans_w ? 1 : 0;
   a.H = nullptr;
+  a.tail_ws = nullptr;
   return a;
 }
 }  // namespace
@@ -194,7 +195,7 @@ static void plinear_bwd_layout(smoe_dtype dt, int d_in, int d_out, int Tk, int g
   off_dybar = off_xbar = (size_t)-1;
   if (!grouped_out) { off_dybar = off; off += align256((size_t)Tk * d_out * es); }
   if (!grouped_in) { off_xbar = off; off += align256((size_t)Tk * d_in * es); }
-  total = off;
+  total = off + S2S_TAIL_WS_BYTES;   // fp32 partial tiles of the input-gradient product's split last round
 }
 
 size_t smoe_plinear_bwd_workspace_bytes(smoe_dtype dtype, int x_rows, int d_in, int d_out, int Tk, int k,
@@ -266,6 +267,7 @@ int smoe_plinear_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *
     bool need_sum = !grouped_in && k > 1;
     void *dst = need_sum ? xbar : dX;   // Xbar is dead once dW is done
     S2SArgs a = make_s2s(dYbar, W, dst, r, d_in, d_out, true, true, 1, grouped_in != 0);
+    a.tail_ws = (float *)((char *)ws + need - S2S_TAIL_WS_BYTES);
     rc = run_s2s(ctx, s, dtype, a);
     if (rc != SMOE_OK) return rc;
     if (need_sum) rc = launch_combine(s, dtype, dst, nullptr, dX, x_rows, k, d_in);
@@ -279,9 +281,10 @@ static inline int hidden_width(smoe_act act, int d_expert) { return act == SMOE_
 size_t smoe_mlp_fwd_workspace_bytes(smoe_dtype dtype, smoe_act act, int T, int k, int d_model, int d_expert,
                                     int training) {
   if (!dtype_ok(dtype) || T < 0 || k < 1 || d_model < 1 || d_expert < 1) return 0;
-  if (training) return 0;
+  if (training) return S2S_TAIL_WS_BYTES;
   size_t es = dtype_size(dtype), Tk = (size_t)T * k;
-  return align256(Tk * hidden_width(act, d_expert) * es) + align256(Tk * d_expert * es) + align256(Tk * d_model * es);
+  return align256(Tk * hidden_width(act, d_expert) * es) + align256(Tk * d_expert * es) +
+         align256(Tk * d_model * es) + S2S_TAIL_WS_BYTES;
 }
 
 int smoe_mlp_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, const void *X, int T, int d_model,
@@ -298,9 +301,10 @@ int smoe_mlp_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
   const int d_h = hidden_width(act, d_expert), Tk = r->Tk;
   if (!width_ok(dtype, d_model) || !width_ok(dtype, d_expert)) return SMOE_ERR_UNSUPPORTED;
   size_t es = dtype_size(dtype);
+  size_t need = smoe_mlp_fwd_workspace_bytes(dtype, act, T, k, d_model, d_expert, nsaved != 0);
+  if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need) return SMOE_ERR_WORKSPACE;
+  float *tail_ws = (float *)((char *)ws + need - S2S_TAIL_WS_BYTES);   // partial tiles of a split last round
   if (nsaved == 0) {
-    size_t need = smoe_mlp_fwd_workspace_bytes(dtype, act, T, k, d_model, d_expert, 0);
-    if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need) return SMOE_ERR_WORKSPACE;
     saved_Hpre = ws;
     saved_H = (char *)saved_Hpre + align256((size_t)Tk * d_h * es);
     saved_Yhat = (char *)saved_H + align256((size_t)Tk * d_expert * es);
@@ -311,6 +315,7 @@ int smoe_mlp_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
   hipStream_t s = (hipStream_t)stream;
   // Hpre = ParallelLinear(X, W1, scattered -> grouped);  H = sigma(Hpre)
   S2SArgs a1 = make_s2s(X, W1, saved_Hpre, r, d_model, d_h, false, false, k, true);
+  a1.tail_ws = tail_ws;
   int rc;
   S2SArgs fused = a1;
   fused.H = saved_H;
@@ -328,6 +333,7 @@ int smoe_mlp_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
   }
   // Y = ParallelLinear(H, W2, p, grouped -> scattered)
   S2SArgs a2 = make_s2s(saved_H, W2, saved_Yhat, r, d_expert, d_model, false, true, 1, false);
+  a2.tail_ws = tail_ws;
   rc = run_s2s(ctx, s, dtype, a2);
   if (rc != SMOE_OK) return rc;
   return launch_combine(s, dtype, saved_Yhat, gates, Y, T, k, d_model);
@@ -338,7 +344,8 @@ int smoe_mlp_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
 size_t smoe_mlp_bwd_workspace_bytes(smoe_dtype dtype, smoe_act act, int T, int k, int d_model, int d_expert) {
   if (!dtype_ok(dtype) || T < 0 || k < 1 || d_model < 1 || d_expert < 1) return 0;
   size_t es = dtype_size(dtype), Tk = (size_t)T * k;
-  return align256(Tk * d_model * es) + align256(Tk * d_expert * es) + align256(Tk * hidden_width(act, d_expert) * es);
+  return align256(Tk * d_model * es) + align256(Tk * d_expert * es) + align256(Tk * hidden_width(act, d_expert) * es) +
+         S2S_TAIL_WS_BYTES;
 }
 
 int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, const void *dY, const void *X, int T,
@@ -373,6 +380,7 @@ int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
   void *dYbar = p;                 p += align256((size_t)Tk * d_model * es);
   void *dH = p;                    p += align256((size_t)Tk * d_expert * es);
   void *dHpre = p;
+  float *tail_ws = (float *)((char *)ws + need - S2S_TAIL_WS_BYTES);   // partial tiles of a split last round
   void *Xbar = dYbar;  // dYbar is dead once dH and dW2 are done; its array then holds Xbar, then dXbar
 
   // ---- second ParallelLinear (grouped in, scattered weighted out)
@@ -384,6 +392,7 @@ int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
   rc = run_dw(ctx, s, dtype, w2);                                                      // groupXTY
   if (rc != SMOE_OK) return rc;
   S2SArgs x2 = make_s2s(dYbar, W2, dH, r, d_expert, d_model, true, true, 1, true);      // dH = dYbar W2^T
+  x2.tail_ws = tail_ws;
   rc = run_s2s(ctx, s, dtype, x2);
   if (rc != SMOE_OK) return rc;
   // ---- activation
@@ -397,9 +406,11 @@ int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
   if (rc != SMOE_OK) return rc;
   if (k == 1) {  // slot id == token id: scatter straight into dX
     S2SArgs x1 = make_s2s(dHpre, W1, dX, r, d_model, d_h, true, true, 1, false);
+    x1.tail_ws = tail_ws;
     return run_s2s(ctx, s, dtype, x1);
   }
   S2SArgs x1 = make_s2s(dHpre, W1, Xbar, r, d_model, d_h, true, true, 1, false);        // grouped -> scattered dXbar
+  x1.tail_ws = tail_ws;
   rc = run_s2s(ctx, s, dtype, x1);
   if (rc != SMOE_OK) return rc;
   return launch_combine(s, dtype, Xbar, nullptr, dX, T, k, d_model);                    // sum the k slots
@@ -434,7 +445,7 @@ S2SArgs dense_s2s(const void *A, const void *W, void *C, const int32_t *offsets,
 size_t smoe_momha_fwd_workspace_bytes(int B, int T, int k, int d_model, int h_expert, int d_head, int training) {
   if (B < 1 || T < 1 || k < 1 || d_model < 1 || h_expert < 1 || d_head < 1) return 0;
   MomhaSizes z = momha_sizes(B, T, k, d_model, h_expert, d_head);
-  return 256 + (training ? 0 : 2 * z.kv + 2 * z.q + z.lse + z.yhat);
+  return 256 + S2S_TAIL_WS_BYTES + (training ? 0 : 2 * z.kv + 2 * z.q + z.lse + z.yhat);
 }
 
 int smoe_momha_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *X, int B, int T, int d_model,
@@ -452,6 +463,7 @@ int smoe_momha_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *X,
   MomhaSizes z = momha_sizes(B, T, k, d_model, h_expert, d_head);
   char *p = (char *)ws;
   int32_t *dense_off = (int32_t *)p;  p += 256;
+  float *tail_ws = (float *)p;  p += S2S_TAIL_WS_BYTES;
   if (n_saved == 0) {
     saved_K = p;  p += z.kv;
     saved_V = p;  p += z.kv;
@@ -464,18 +476,19 @@ int smoe_momha_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *X,
   rc = launch_dense_offsets(s, dense_off, N);
   if (rc != SMOE_OK) return rc;
   // V = X W_V, K = X W_K
-  rc = run_s2s(ctx, s, dtype, dense_s2s(X, W_V, saved_V, dense_off, N, d_model, d_out, false));
+  auto product = [&](S2SArgs a) { a.tail_ws = tail_ws; return run_s2s(ctx, s, dtype, a); };
+  rc = product(dense_s2s(X, W_V, saved_V, dense_off, N, d_model, d_out, false));
   if (rc != SMOE_OK) return rc;
-  rc = run_s2s(ctx, s, dtype, dense_s2s(X, W_K, saved_K, dense_off, N, d_model, d_out, false));
+  rc = product(dense_s2s(X, W_K, saved_K, dense_off, N, d_model, d_out, false));
   if (rc != SMOE_OK) return rc;
   // Q = ParallelLinear(X, W_Q, o, no p, scattered -> scattered)
-  rc = run_s2s(ctx, s, dtype, make_s2s(X, W_Q, saved_Q, r, d_model, d_out, false, false, k, false));
+  rc = product(make_s2s(X, W_Q, saved_Q, r, d_model, d_out, false, false, k, false));
   if (rc != SMOE_OK) return rc;
   // Ohat = Attention(Q, K, V)
   rc = launch_attn_fwd(s, saved_Q, saved_K, saved_V, saved_Ohat, saved_LSE, B, T, k, h_expert);
   if (rc != SMOE_OK) return rc;
   // O = ParallelLinear(Ohat, W_O, o, p, scattered -> scattered)
-  rc = run_s2s(ctx, s, dtype, make_s2s(saved_Ohat, W_O, saved_Yhat, r, d_out, d_model, false, false, 1, false));
+  rc = product(make_s2s(saved_Ohat, W_O, saved_Yhat, r, d_out, d_model, false, false, 1, false));
   if (rc != SMOE_OK) return rc;
   return launch_combine(s, dtype, saved_Yhat, gates, O, N, k, d_model);
 }
@@ -485,7 +498,8 @@ size_t smoe_momha_bwd_workspace_bytes(int B, int T, int k, int d_model, int h_ex
   MomhaSizes z = momha_sizes(B, T, k, d_model, h_expert, d_head);
   // dense offsets, dOhat, dQ, dK, dV, three partial dX, delta, and the ParallelLinear backward scratch
   // (a grouped [Tk, d_model] and a grouped [Tk, d_out] array, used by both projections in turn)
-  return 256 + 2 * z.q + 2 * z.kv + 3 * z.x + smoe_attention_bwd_workspace_bytes(B, T, k, h_expert) + z.yhat + z.q;
+  return 256 + 2 * z.q + 2 * z.kv + 3 * z.x + smoe_attention_bwd_workspace_bytes(B, T, k, h_expert) + z.yhat + z.q +
+         S2S_TAIL_WS_BYTES;
 }
 
 int smoe_momha_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *dO, const void *X, int B, int T,
@@ -514,7 +528,8 @@ int smoe_momha_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *dO
   void *dXv = p;    p += z.x;
   void *attn_ws = p;  p += smoe_attention_bwd_workspace_bytes(B, T, k, h_expert);
   void *sub = p;
-  const size_t sub_bytes = z.yhat + z.q;
+  const size_t sub_bytes = z.yhat + z.q + S2S_TAIL_WS_BYTES;
+  float *tail_ws = (float *)((char *)sub + z.yhat + z.q);   // where the ParallelLinear backward puts its own, too
   hipStream_t s = (hipStream_t)stream;
   rc = launch_dense_offsets(s, dense_off, N);
   if (rc != SMOE_OK) return rc;
@@ -534,9 +549,12 @@ int smoe_momha_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *dO
   if (rc != SMOE_OK) return rc;
   rc = run_dw(ctx, s, dtype, wv);
   if (rc != SMOE_OK) return rc;
-  rc = run_s2s(ctx, s, dtype, dense_s2s(dK, W_K, dXk, dense_off, N, d_model, d_out, true));
+  S2SArgs xk = dense_s2s(dK, W_K, dXk, dense_off, N, d_model, d_out, true);
+  S2SArgs xv = dense_s2s(dV, W_V, dXv, dense_off, N, d_model, d_out, true);
+  xk.tail_ws = xv.tail_ws = tail_ws;
+  rc = run_s2s(ctx, s, dtype, xk);
   if (rc != SMOE_OK) return rc;
-  rc = run_s2s(ctx, s, dtype, dense_s2s(dV, W_V, dXv, dense_off, N, d_model, d_out, true));
+  rc = run_s2s(ctx, s, dtype, xv);
   if (rc != SMOE_OK) return rc;
   return launch_add3(s, dXq, dXk, dXv, dX, (size_t)N * d_model);
 }

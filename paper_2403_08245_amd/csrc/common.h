@@ -78,6 +78,9 @@ struct S2SArgs {      // C[out(i), :] = A[in(i), :] * op(W[e(i)])   for sorted r
   int ldw;            // row stride of W[e] (= d_out)
   size_t w_stride;    // elements between experts (= d_in * d_out)
   int trans_w;        // 0: op(W) = W (K = d_in, N = d_out); 1: op(W) = W^T (K = d_out, N = d_in)
+  // Optional scratch for splitting the contraction of the last, partly filled round of tiles over the
+  // compute units that would otherwise idle (S2S_TAIL_WS_BYTES of device memory, or NULL: no split).
+  float *tail_ws;
   // Optional fused SwiGLU of Alg. 3 (forward, expert-sorted output only): W's columns are
   // [gate | up] halves of width N / 2 and H [*, N / 2] receives silu(gate) * up; C may then be
   // NULL when the pre-activation is not kept.
@@ -97,6 +100,7 @@ bool dw_mfma_supported(const DWArgs &a);
 int launch_s2s_mfma(hipStream_t s, const S2SArgs &a, int num_cu);
 int launch_dw_mfma(hipStream_t s, const DWArgs &a, int num_cu);
 // persistent tile-stream kernels (gemm_stream.hip)
+constexpr size_t S2S_TAIL_WS_BYTES = (size_t)256 * 256 * 256 * sizeof(float);   // 256 partial tiles of 256 x 256 fp32
 bool s2s_stream_supported(const S2SArgs &a);
 bool s2s_stream_swiglu_supported(const S2SArgs &a);
 int launch_s2s_stream(hipStream_t s, const S2SArgs &a);

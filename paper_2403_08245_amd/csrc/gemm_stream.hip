@@ -135,6 +135,23 @@ __device__ __forceinline__ void store_wave_tile_swiglu(const f32x16 (&acc)[FR][F
   }
 }
 
+// A wavefront's 128 x 128 accumulators as fp32 into a 256-wide partial tile (chunks of a split contraction).
+__device__ __forceinline__ void store_wave_partial(const f32x16 (&acc)[FR][FR], float *dst, int lane) {
+  __asm__ volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+  for (int fm = 0; fm < FR; ++fm)
+#pragma unroll
+    for (int fn = 0; fn < FR; ++fn) {
+      sched_fence();
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float4 v = make_float4(acc_read(acc[fm][fn][4 * g]), acc_read(acc[fm][fn][4 * g + 1]), acc_read(acc[fm][fn][4 * g + 2]),
+                               acc_read(acc[fm][fn][4 * g + 3]));
+        *reinterpret_cast<float4 *>(dst + (size_t)(fm * 32 + (lane & 31)) * TB + fn * 32 + 8 * g + 4 * (lane >> 5)) = v;
+      }
+    }
+}
+
 // One half-step of the contraction: 32 matrix instructions on the landed stage `cur`, the
 // fragment reads of its second half and of the next stage's first half riding behind them, and
 // the eight loads of the stage being refilled, one per four matrix instructions.  FIRST starts
@@ -191,7 +208,68 @@ struct S2STile {
   int seq;                    // position in this block's tile list (-1 before the first)
   int ord;                    // running number of the tile among the block's valid tiles
   int e, row0, row_end, n0;
+  int h0, hn;                 // first half-step and number of half-steps this block contributes
+  int part;                   // -1: the whole contraction, result stored directly; else index of the fp32 partial
 };
+
+// How the tiles of one launch are dealt to the G persistent blocks.  Tiles are numbered densely
+// (groups of group_m M-tiles x all N-tiles); block b takes numbers seq * G + slot(b) for the `rounds`
+// full rounds.  The remaining `rest` < G tiles would leave G - rest blocks idle for a whole tile, so
+// their contraction is cut into `split` chunks of `chunk` half-steps, one block each; the chunks leave
+// fp32 partial tiles that a second kernel adds in chunk order (deterministic) and stores.
+struct TilePlan {
+  int m_tiles, rounds, rest, split, chunk;
+};
+// A chunk's fp32 partial tile costs a 256 KB write and a 256 KB read on top of the second kernel's launch,
+// about what 48 half-steps of multiplying take: a split must shorten the last round by more than that.
+constexpr int SPLIT_MIN_SAVED = 64;
+// Largest number of chunks <= max_split (and <= 4) that pays, with the chunk length; 1 = keep whole tiles.
+__host__ __device__ inline int choose_split(int nh, int max_split, bool static4, int &chunk) {
+  for (int s = max_split < 4 ? max_split : 4; s > 1; --s) {
+    int c = (nh + s - 1) / s;
+    if (static4) c = (c + 3) & ~3;
+    if ((s - 1) * c < nh && nh - c >= SPLIT_MIN_SAVED) {
+      chunk = c;
+      return s;
+    }
+  }
+  chunk = nh;
+  return 1;
+}
+__device__ __forceinline__ TilePlan plan_tiles(const int32_t *offsets, int E, int tiles_n, int nh, int G, bool static4,
+                                               bool may_split, int lane) {
+  int sum = 0;
+  for (int c0 = 0; c0 < E; c0 += 64) {
+    int x = c0 + lane;
+    int n = x < E ? (offsets[x + 1] - offsets[x] + TB - 1) / TB : 0;
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) n += __shfl_xor(n, d, 64);
+    sum += n;
+  }
+  TilePlan p;
+  p.m_tiles = __builtin_amdgcn_readfirstlane(sum);
+  const long long total = (long long)p.m_tiles * tiles_n;
+  p.rounds = (int)(total / G);
+  p.rest = (int)(total - (long long)p.rounds * G);
+  p.split = 1;
+  p.chunk = nh;
+  if (may_split && p.rest > 0) p.split = choose_split(nh, G / p.rest, static4, p.chunk);
+  return p;
+}
+// dense tile number -> (M-tile, N-tile): groups of group_m M-tiles (the last group may be narrower)
+__device__ __forceinline__ void tile_coords(int w, int m_tiles, int tiles_n, int group_m, int &mt, int &nt) {
+  const int per_group = group_m * tiles_n, full = m_tiles / group_m;
+  int grp = w / per_group;
+  if (grp < full) {
+    int in_grp = w - grp * per_group;
+    mt = grp * group_m + in_grp % group_m;
+    nt = in_grp / group_m;
+  } else {
+    int last = m_tiles - full * group_m, in_grp = w - full * per_group;
+    mt = full * group_m + in_grp % last;
+    nt = in_grp / last;
+  }
+}
 
 template <bool TRANS_W> struct S2SStreamOps {
   // Sources of the loader's current tile: wave-uniform bases plus per-lane 32-bit byte offsets at
@@ -222,8 +300,7 @@ template <bool TRANS_W> struct S2SStreamOps {
 // half-steps, so every tile starts in LDS stage 0 and the loop is written out four slots at a time with the
 // stage as a compile-time constant: all LDS addresses become a loop-invariant register plus an immediate.
 template <bool TRANS_W, bool SCATTER_OUT, int ACT = 0, bool STATIC4 = false>
-__global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int tiles_n, int group_m, int total_vids,
-                                                                 uint32_t magic_a) {
+__global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int tiles_n, int group_m, uint32_t magic_a) {
   static_assert(ACT == 0 || (!TRANS_W && !SCATTER_OUT), "the fused activation belongs to the forward, sorted-output product");
   constexpr bool SWIGLU = ACT != 0;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -242,25 +319,34 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
   for (int i = threadIdx.x; i <= a.E; i += NTHREADS) s_off[i] = a.offsets[i];
   __syncthreads();
 
-  // next valid tile of this block after t (tiles whose M index lies past the last segment are skipped)
+  const TilePlan plan = plan_tiles(s_off, a.E, tiles_n, nh, G, STATIC4, ACT == 0 && a.tail_ws != nullptr, lane);
+  // next tile (or chunk of a tile of the last round) of this block after t
   auto next_tile = [&](S2STile &t) -> bool {
-    const int per_group = group_m * tiles_n;
-    for (int seq = t.seq + 1;; ++seq) {
-      int vid = seq * G + slot_in_round;
-      if (vid >= total_vids) return false;
-      int grp = vid / per_group, in_grp = vid % per_group;
-      int mt = grp * group_m + in_grp % group_m, nt = in_grp / group_m;
-      int e, row0, row_end;
-      if (locate_tile(s_off, a.E, mt, lane, e, row0, row_end)) {
-        t.seq = seq;
-        t.ord += 1;
-        t.e = __builtin_amdgcn_readfirstlane(e);
-        t.row0 = __builtin_amdgcn_readfirstlane(row0);
-        t.row_end = __builtin_amdgcn_readfirstlane(row_end);
-        t.n0 = nt * (SWIGLU ? TB / 2 : TB);   // SwiGLU tiles hold 128 gate columns and the 128 up columns pairing with them
-        return true;
-      }
+    const int seq = t.seq + 1;
+    int w, chunk = 0;
+    bool split = false;
+    if (seq < plan.rounds) {
+      w = seq * G + slot_in_round;
+    } else if (seq == plan.rounds && slot_in_round < plan.rest * plan.split) {
+      w = plan.rounds * G + slot_in_round / plan.split;
+      chunk = slot_in_round % plan.split;
+      split = plan.split > 1;
+    } else {
+      return false;
     }
+    int mt, nt, e, row0, row_end;
+    tile_coords(w, plan.m_tiles, tiles_n, group_m, mt, nt);
+    locate_tile(s_off, a.E, mt, lane, e, row0, row_end);
+    t.seq = seq;
+    t.ord += 1;
+    t.e = __builtin_amdgcn_readfirstlane(e);
+    t.row0 = __builtin_amdgcn_readfirstlane(row0);
+    t.row_end = __builtin_amdgcn_readfirstlane(row_end);
+    t.n0 = nt * (SWIGLU ? TB / 2 : TB);   // SwiGLU tiles hold 128 gate columns and the 128 up columns pairing with them
+    t.h0 = split ? chunk * plan.chunk : 0;
+    t.hn = split ? min(nh, t.h0 + plan.chunk) - t.h0 : nh;
+    t.part = split ? (w - plan.rounds * G) * plan.split + chunk : -1;
+    return true;
   };
   // order indices of a tile's 256 rows -> s_idx[ord % 3] (rows past the segment repeat its last row)
   auto fetch_rows = [&](const S2STile &t) {
@@ -273,9 +359,10 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
   ops.uwave = uwave;
   ops.b_step = TRANS_W ? (uint32_t)(HK * 2) : (uint32_t)(HK * 2) * (uint32_t)a.ldw;
   auto setup_pointers = [&](const S2STile &t) {
-    ops.base_b = (const char *)((const bf16_t *)a.W + (size_t)t.e * a.w_stride);
+    // the tile's (chunk of the) contraction starts at half-step h0
+    ops.base_b = (const char *)((const bf16_t *)a.W + (size_t)t.e * a.w_stride) + (size_t)t.h0 * ops.b_step;
     // gathered rows are addressed from the start of A, expert-sorted rows from the tile's first row
-    ops.base_a = (const char *)(a.a_map.o ? A : A + (size_t)t.row0 * a.K);
+    ops.base_a = (const char *)(a.a_map.o ? A : A + (size_t)t.row0 * a.K) + (size_t)t.h0 * (HK * 2);
     const int *idx = &s_idx[t.ord % 3][0];
     const uint32_t row_bytes = (uint32_t)a.K * 2u;
 #pragma unroll
@@ -313,7 +400,7 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
   };
 
   // ---- open the first two tiles
-  S2STile lt{-1, -1, 0, 0, 0, 0};
+  S2STile lt{-1, -1, 0, 0, 0, 0, 0, 0, -1};
   if (!next_tile(lt)) return;
   S2STile ct = lt;             // the multiplying side starts on the same tile
   S2STile upcoming = lt;       // tile the loader will open next
@@ -328,10 +415,10 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
   // loader moves one slot on; at a tile end it opens the upcoming tile and requests the rows of the one after
   auto advance_loader = [&]() {
     if (!loader_live) return;
-    if (++ops.step < nh) return;
+    if (++ops.step < lt.hn) return;
     if (!have_upcoming) {
       loader_live = false;
-      ops.step = nh - 1;      // slots past the end repeat the last stage's addresses
+      ops.step = lt.hn - 1;   // slots past the end repeat the last stage's addresses
       return;
     }
     lt = upcoming;
@@ -391,7 +478,7 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
       static_slot(std::false_type{}, I2{});
       open_slot();
       static_slot(std::false_type{}, I3{});
-      for (int h = 4; h < nh; h += 4) {
+      for (int h = 4; h < ct.hn; h += 4) {
         open_slot();
         static_slot(std::false_type{}, I0{});
         open_slot();
@@ -403,7 +490,7 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
       }
     } else {
       one_slot(std::true_type{});
-      for (int h = 1; h < nh; ++h) {
+      for (int h = 1; h < ct.hn; ++h) {
         open_slot();
         one_slot(std::false_type{});
       }
@@ -420,11 +507,46 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
     };
     if (SWIGLU)
       store_wave_tile_swiglu<ACT == 1>(acc, patch, dst_row, (bf16_t *)a.C, (bf16_t *)a.H, a.N / 2, ct.n0 + wn * (TB / 4), lane);
+    else if (ct.part >= 0)
+      store_wave_partial(acc, a.tail_ws + (size_t)ct.part * TB * TB + (size_t)(wm * (TB / 2)) * TB + wn * (TB / 2), lane);
     else
       store_wave_tile(acc, patch, dst_row, (bf16_t *)a.C, a.N, ct.n0 + wn * (TB / 2), a.N, lane);
     if (!next_tile(ct)) break;
   }
   wait_loads<0>();
+}
+
+// Second pass of a split last round: adds the chunks' fp32 partial tiles in chunk order, rounds once and
+// stores the rows where the unsplit epilogue would have (expert-sorted or scattered).  One block per tile of
+// the last round; the plan is recomputed from the same inputs as in the main kernel.
+template <bool SCATTER_OUT>
+__global__ void __launch_bounds__(256) s2s_tail_reduce_kernel(S2SArgs a, int tiles_n, int group_m, int G, int static4) {
+  __shared__ int s_off[MAX_E + 1];
+  const int lane = threadIdx.x & 63;
+  for (int i = threadIdx.x; i <= a.E; i += 256) s_off[i] = a.offsets[i];
+  __syncthreads();
+  const TilePlan plan = plan_tiles(s_off, a.E, tiles_n, a.K / HK, G, static4 != 0, true, lane);
+  if (plan.split <= 1 || (int)blockIdx.x >= plan.rest) return;
+  int mt, nt, e, row0, row_end;
+  tile_coords(plan.rounds * G + (int)blockIdx.x, plan.m_tiles, tiles_n, group_m, mt, nt);
+  locate_tile(s_off, a.E, mt, lane, e, row0, row_end);
+  const int n0 = nt * TB;
+  const float *part = a.tail_ws + (size_t)blockIdx.x * plan.split * TB * TB;
+  bf16_t *C = (bf16_t *)a.C;
+  for (int i = threadIdx.x; i < TB * TB / 4; i += 256) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int c = 0; c < plan.split; ++c) {
+      const float4 v = reinterpret_cast<const float4 *>(part + (size_t)c * TB * TB)[i];
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    const int row = row0 + (i * 4) / TB, col = n0 + (i * 4) % TB;
+    if (row < row_end && col < a.N) {
+      const int dst = SCATTER_OUT ? a.c_map.o[row] : row;
+      bf16x4 o;
+      o[0] = (bf16_t)acc.x; o[1] = (bf16_t)acc.y; o[2] = (bf16_t)acc.z; o[3] = (bf16_t)acc.w;
+      *reinterpret_cast<bf16x4 *>(C + (size_t)dst * a.N + col) = o;
+    }
+  }
 }
 
 // ======================================================================================
@@ -633,13 +755,20 @@ template <bool TRANS_W, bool SCATTER_OUT, int ACT, bool STATIC4> int launch_s2s_
   static int attr_rc = set_lds_limit(s2s_stream_kernel<TRANS_W, SCATTER_OUT, ACT, STATIC4>, STREAM_LDS_BYTES);
   if (attr_rc != SMOE_OK) return attr_rc;
   int tiles_n = ACT ? ceil_div(a.N / 2, TB / 2) : ceil_div(a.N, TB);
-  int tiles_m = ceil_div(a.Tk, TB) + a.E;     // upper bound on sum_e ceil(n_e / 256)
+  long long tiles_m = ceil_div(a.Tk, TB) + a.E;     // upper bound on sum_e ceil(n_e / 256)
   int group_m = 4;
-  long long total = (long long)ceil_div(tiles_m, group_m) * group_m * tiles_n;
-  if (total > 0x7fffffffLL) return SMOE_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL((s2s_stream_kernel<TRANS_W, SCATTER_OUT, ACT, STATIC4>), dim3(STREAM_GRID), dim3(NTHREADS), STREAM_LDS_BYTES, s, a, tiles_n,
-                     group_m, (int)total, division_magic(a.a_map.o ? a.a_map.fan : 1));
+  if (tiles_m * tiles_n > 0x7fffffffLL) return SMOE_ERR_UNSUPPORTED;
+  S2SArgs args = a;
+  int chunk;
+  if (ACT != 0 || choose_split(a.K / HK, 4, STATIC4, chunk) == 1) args.tail_ws = nullptr;   // too short to pay: no second kernel
+  hipLaunchKernelGGL((s2s_stream_kernel<TRANS_W, SCATTER_OUT, ACT, STATIC4>), dim3(STREAM_GRID), dim3(NTHREADS), STREAM_LDS_BYTES, s, args, tiles_n,
+                     group_m, division_magic(a.a_map.o ? a.a_map.fan : 1));
   SMOE_LAUNCH_CHECK();
+  if (args.tail_ws) {   // adds and stores the partial tiles of a split last round (no-op when nothing was split)
+    hipLaunchKernelGGL(s2s_tail_reduce_kernel<SCATTER_OUT>, dim3(STREAM_GRID - 1), dim3(256), 0, s, a, tiles_n, group_m,
+                       STREAM_GRID, STATIC4 ? 1 : 0);
+    SMOE_LAUNCH_CHECK();
+  }
   return SMOE_OK;
 }
 
@@ -651,7 +780,6 @@ int launch_dw_stream_impl(hipStream_t s, const DWArgs &a) {
   SMOE_LAUNCH_CHECK();
   return SMOE_OK;
 }
-
 }  // namespace
 
 // The persistent kernel keeps three half-steps in flight across tile boundaries, so a tile must

@@ -66,7 +66,7 @@ def _check(name, gpu, ref, tol, scale=None):
     return err
 
 
-def _run_fullsize(smoe, cfg, seed, tokens_per_expert, dw_samples, backward=True):
+def _run_fullsize(smoe, cfg, seed, tokens_per_expert, dw_samples, backward=True, last_rows=0):
     t0 = time.time()
     td = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     tol = TOL[td]
@@ -99,6 +99,12 @@ def _run_fullsize(smoe, cfg, seed, tokens_per_expert, dw_samples, backward=True)
     inv = np.empty(cfg.Tk, dtype=np.int64)
     inv[o] = np.arange(cfg.Tk)                     # sorted position of every slot
     toks = _sample_tokens(ei, cfg.E, tokens_per_expert, seed)
+    if last_rows:
+        # tokens with a slot among the last expert-sorted rows: the output tiles the persistent kernels reach
+        # last, where a partly filled last round has its contraction split over several blocks
+        tail = np.unique(o[cfg.Tk - last_rows:] // cfg.k)
+        extra = np.random.default_rng(seed + 2).choice(tail, size=min(8, len(tail)), replace=False).tolist()
+        toks = toks + sorted(set(extra) - set(toks), key=lambda t: tuple(sorted(ei[t].tolist())))
     Yc, dXc, dgc = Y.float().cpu().numpy(), None, None
     if backward:
         dXc, dgc = dX.float().cpu().numpy(), dg.cpu().numpy()
@@ -150,7 +156,22 @@ def test_C2_small_bf16_sampled(smoe):
 
 
 def test_C3_mixtral_layer_sampled(smoe):
-    _run_fullsize(smoe, si.CONFIGS["C3"], 0, tokens_per_expert=2, dw_samples=1)
+    _run_fullsize(smoe, si.CONFIGS["C3"], 0, tokens_per_expert=2, dw_samples=1, last_rows=512)
+
+
+@pytest.mark.parametrize("d_model,d_expert", [(3072, 2816), (3104, 2848)])
+def test_partial_last_round_split_sampled(smoe, d_model, d_expert):
+    """Just over 256 output tiles per product, so the persistent kernels run one full round of whole tiles
+    and then a round under a quarter full, whose long contraction is cut into chunks run by the idle blocks
+    (fp32 partial tiles added by a second kernel).  Contractions that are and are not a multiple of 128;
+    the sample takes rows from the first tiles and from the last ones."""
+    cfg = si.custom(f"tail{d_model}", T=2560, d_model=d_model, d_expert=d_expert, E=8, k=2, act=si.ACT_GELU, dtype="bf16")
+    _, off = np.unique(oracle.topk_gate(si.mlp_case(cfg, 12)["logits"].numpy(), cfg.k)[0], return_counts=True)
+    m_tiles = int(((off + 255) // 256).sum())
+    for width in (d_model, d_expert):     # output widths of the second product / first input gradient, and of dH
+        tiles = m_tiles * ((width + 255) // 256)
+        assert tiles > 256 and tiles % 256 <= 64, (m_tiles, tiles)
+    _run_fullsize(smoe, cfg, 12, tokens_per_expert=2, dw_samples=1, last_rows=600)
 
 
 def test_C4_granular_sampled(smoe):
