@@ -16,6 +16,7 @@ bool width_ok(smoe_dtype dt, int d) { return d > 0 && d % (int)(16 / dtype_size(
 bool dtype_ok(int dt) { return dt == SMOE_F32 || dt == SMOE_BF16; }
 
 int run_s2s(smoe_ctx *ctx, hipStream_t s, smoe_dtype dt, const S2SArgs &a) {
+  if (dt == SMOE_BF16 && ctx->kernel_mode == 0 && s2s_decode_supported(a)) return launch_s2s_decode(s, a);
   if (dt == SMOE_BF16 && ctx->kernel_mode == 0 && s2s_stream_supported(a)) return launch_s2s_stream(s, a);
   if (dt == SMOE_BF16 && ctx->kernel_mode != 1 && s2s_mfma_supported(a)) return launch_s2s_mfma(s, a, ctx->num_cu);
   return launch_s2s_plain(s, dt, a);
@@ -319,11 +320,12 @@ int smoe_mlp_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
   int rc;
   S2SArgs fused = a1;
   fused.H = saved_H;
-  if (act == SMOE_ACT_SWIGLU && dtype == SMOE_BF16 && ctx->kernel_mode == 0 && s2s_stream_swiglu_supported(fused)) {
+  if (act == SMOE_ACT_SWIGLU && dtype == SMOE_BF16 && ctx->kernel_mode == 0 &&
+      (s2s_decode_supported(fused) || s2s_stream_swiglu_supported(fused))) {
     // SwiGLU in the product's epilogue: H comes straight from the fp32 accumulators, and the
     // pre-activation is written only when the caller keeps it for the backward pass
     if (nsaved == 0) fused.C = nullptr;
-    rc = launch_s2s_stream(s, fused);
+    rc = s2s_decode_supported(fused) ? launch_s2s_decode(s, fused) : launch_s2s_stream(s, fused);
     if (rc != SMOE_OK) return rc;
   } else {
     rc = run_s2s(ctx, s, dtype, a1);

@@ -104,5 +104,9 @@ constexpr size_t S2S_TAIL_WS_BYTES = (size_t)256 * 256 * 256 * sizeof(float);   
 bool s2s_stream_supported(const S2SArgs &a);
 bool s2s_stream_swiglu_supported(const S2SArgs &a);
 int launch_s2s_stream(hipStream_t s, const S2SArgs &a);
+// Small-batch (decoding) forward products: 32-row tiles, one wavefront each, bound by the weight stream.
+// Takes a.H like the persistent kernel (fused SwiGLU).
+bool s2s_decode_supported(const S2SArgs &a);
+int launch_s2s_decode(hipStream_t s, const S2SArgs &a);
 bool dw_stream_supported(const DWArgs &a);
 int launch_dw_stream(hipStream_t s, const DWArgs &a);

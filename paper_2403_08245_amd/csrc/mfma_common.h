@@ -105,17 +105,18 @@ __device__ __forceinline__ bf16x8 tr_frag(const char *tile, int cbase, int kk, i
 // byte offset inside an operand tile of a wavefront's load instruction (both layouts: 1 KB each)
 __device__ __forceinline__ int inst_off(int wave, int inst) { return (wave * NLD + inst) * 1024; }
 
-// Finds expert and first row of M-tile `tile` when each expert's segment is cut into 256-row
-// tiles.  Every wavefront runs the search on its own: lane x looks at expert c0 + x, a wave
+// Finds expert and first row of M-tile `tile` when each expert's segment is cut into tiles of
+// ROWS rows.  Every wavefront runs the search on its own: lane x looks at expert c0 + x, a wave
 // prefix sum counts the tiles before it, a ballot picks the expert that owns `tile`.
-__device__ __forceinline__ bool locate_tile(const int32_t *offsets, int E, int tile, int lane, int &e, int &row0,
+template <int ROWS>
+__device__ __forceinline__ bool locate_rows(const int32_t *offsets, int E, int tile, int lane, int &e, int &row0,
                                             int &row_end) {
   int base = 0;
   for (int c0 = 0; c0 < E; c0 += 64) {
     int x = c0 + lane;
     int lo = 0, hi = 0;
     if (x < E) { lo = offsets[x]; hi = offsets[x + 1]; }
-    int nt = (hi - lo + TB - 1) / TB;
+    int nt = (hi - lo + ROWS - 1) / ROWS;
     int incl = nt;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -130,13 +131,17 @@ __device__ __forceinline__ bool locate_tile(const int32_t *offsets, int E, int t
       int first = __ffsll((long long)owns) - 1;
       int before = __builtin_amdgcn_readfirstlane(__shfl(incl - nt, first, 64));
       e = c0 + first;
-      row0 = __builtin_amdgcn_readfirstlane(__shfl(lo, first, 64)) + (tile - base - before) * TB;
+      row0 = __builtin_amdgcn_readfirstlane(__shfl(lo, first, 64)) + (tile - base - before) * ROWS;
       row_end = __builtin_amdgcn_readfirstlane(__shfl(hi, first, 64));
       return true;
     }
     base += total;
   }
   return false;
+}
+__device__ __forceinline__ bool locate_tile(const int32_t *offsets, int E, int tile, int lane, int &e, int &row0,
+                                            int &row_end) {
+  return locate_rows<TB>(offsets, E, tile, lane, e, row0, row_end);
 }
 
 // Blocks are dealt round-robin to the 8 XCDs; give each XCD a contiguous run of tile ids so

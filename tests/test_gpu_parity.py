@@ -241,6 +241,22 @@ def test_mlp_fused_swiglu_ragged_widths(smoe, d_model, d_expert):
     assert torch.equal(Yt, Yi)
 
 
+@pytest.mark.parametrize("act", [si.ACT_GELU, si.ACT_SWIGLU])
+@pytest.mark.parametrize("shape", [(40, 4, 16, 160, 96, 0), (100, 2, 8, 256, 224, 5), (3, 2, 64, 64, 32, 0)])
+def test_mlp_small_batches_take_the_decode_kernels(smoe, shape, act):
+    """At most 32 routed rows per expert on average: the forward products run as 32-row tiles, one
+    wavefront each.  Widths that leave the last 128-column tile (64 gate columns for SwiGLU) partly empty,
+    experts with several tiles (five of eight experts masked out) and with none, training and inference."""
+    T, k, E, d_model, d_expert, masked = shape
+    cfg = si.custom(f"decode{T}", T=T, d_model=d_model, d_expert=d_expert, E=E, k=k, act=act, dtype="bf16",
+                    masked_experts=masked)
+    assert T * k <= 32 * E
+    case, (X, W1, W2, dYc, r, gg) = _mlp_parity(smoe, cfg, 13)
+    Yt, _ = smoe.mlp_fwd(X, W1, W2, r, cfg.k, gg, cfg.act, training=True)
+    Yi, _ = smoe.mlp_fwd(X, W1, W2, r, cfg.k, gg, cfg.act, training=False)
+    assert torch.equal(Yt, Yi)
+
+
 def test_mlp_k1_and_k_equals_E(smoe):
     _mlp_parity(smoe, si.custom("k1", T=130, d_model=64, d_expert=64, E=4, k=1, act=si.ACT_SWIGLU, dtype="bf16"), 5)
     _mlp_parity(smoe, si.custom("kE", T=50, d_model=64, d_expert=32, E=4, k=4, act=si.ACT_GELU, dtype="f32"), 6)
