@@ -237,6 +237,60 @@ __global__ void __launch_bounds__(64) route_place_kernel(const int32_t *__restri
   }
 }
 
+// All three steps in one wavefront when the slots fit one chunk (decoding batches): histogram, exclusive
+// scan over the experts, stable placement.  Nothing passes through global memory in between.
+__global__ void __launch_bounds__(64) route_single_chunk_kernel(const int32_t *__restrict__ expert_idxs, int Tk, int E,
+                                                                int32_t *__restrict__ offsets,
+                                                                int32_t *__restrict__ sorted_e,
+                                                                int32_t *__restrict__ sorted_s) {
+  extern __shared__ int32_t next[];  // rows per expert, then next free position per expert
+  const int lane = threadIdx.x;
+  for (int e = lane; e < E; e += 64) next[e] = 0;
+  __syncthreads();
+  for (int s = lane; s < Tk; s += 64) atomicAdd(&next[clamp_expert(expert_idxs[s], E)], 1);
+  __syncthreads();
+  int run = 0;
+  for (int c0 = 0; c0 < E; c0 += 64) {
+    const int e = c0 + lane;
+    const int n = e < E ? next[e] : 0;
+    int incl = n;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      int up = __shfl_up(incl, d, 64);
+      if (lane >= d) incl += up;
+    }
+    if (e < E) {
+      next[e] = run + incl - n;
+      offsets[e] = run + incl - n;
+    }
+    run += __shfl(incl, 63, 64);
+  }
+  if (lane == 0) offsets[E] = run;
+  __syncthreads();
+  const int nbits = 32 - __clz(max(E - 1, 1));
+  const unsigned long long lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  for (int s0 = 0; s0 < Tk; s0 += 64) {
+    const int s = s0 + lane;
+    const bool live = s < Tk;
+    const int e = live ? clamp_expert(expert_idxs[s], E) : 0;
+    unsigned long long peers = __ballot(live);
+    for (int b = 0; b < nbits; ++b) {
+      unsigned long long set = __ballot(live && ((e >> b) & 1));
+      peers &= ((e >> b) & 1) ? set : ~set;
+    }
+    const int rank = __popcll(peers & lt_mask);
+    int pos = 0;
+    if (live) pos = next[e] + rank;
+    __syncthreads();
+    if (live && rank == 0) next[e] += __popcll(peers);  // lowest lane of each expert updates
+    __syncthreads();
+    if (live) {
+      sorted_e[pos] = e;
+      sorted_s[pos] = s;
+    }
+  }
+}
+
 size_t route_workspace_bytes(int Tk, int E) {
   size_t nchunk = (size_t)ceil_div(Tk > 0 ? Tk : 1, ROUTE_CHUNK);
   return align256(nchunk * (size_t)E * sizeof(int32_t));
@@ -247,6 +301,11 @@ int launch_route(hipStream_t s, const int32_t *expert_idxs, int Tk, int E, int32
   int nchunk = ceil_div(Tk > 0 ? Tk : 1, ROUTE_CHUNK);
   int32_t *counts = (int32_t *)ws;
   size_t shm = (size_t)E * sizeof(int32_t);
+  if (nchunk == 1) {
+    hipLaunchKernelGGL(route_single_chunk_kernel, dim3(1), dim3(64), shm, s, expert_idxs, Tk, E, offsets, sorted_e, sorted_s);
+    SMOE_LAUNCH_CHECK();
+    return SMOE_OK;
+  }
   hipLaunchKernelGGL(route_count_kernel, dim3(nchunk), dim3(64), shm, s, expert_idxs, Tk, E, counts);
   SMOE_LAUNCH_CHECK();
   hipLaunchKernelGGL(route_scan_kernel, dim3(1), dim3(1024), shm, s, counts, nchunk, E, offsets, Tk);
