@@ -517,8 +517,9 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
 }
 
 // Second pass of a split last round: adds the chunks' fp32 partial tiles in chunk order, rounds once and
-// stores the rows where the unsplit epilogue would have (expert-sorted or scattered).  One block per tile of
-// the last round; the plan is recomputed from the same inputs as in the main kernel.
+// stores the rows where the unsplit epilogue would have (expert-sorted or scattered).  TAIL_SLICES blocks
+// (32 rows each) per tile of the last round; the plan is recomputed from the same inputs as in the main kernel.
+constexpr int TAIL_SLICES = 8;
 template <bool SCATTER_OUT>
 __global__ void __launch_bounds__(256) s2s_tail_reduce_kernel(S2SArgs a, int tiles_n, int group_m, int G, int static4) {
   __shared__ int s_off[MAX_E + 1];
@@ -533,7 +534,8 @@ __global__ void __launch_bounds__(256) s2s_tail_reduce_kernel(S2SArgs a, int til
   const int n0 = nt * TB;
   const float *part = a.tail_ws + (size_t)blockIdx.x * plan.split * TB * TB;
   bf16_t *C = (bf16_t *)a.C;
-  for (int i = threadIdx.x; i < TB * TB / 4; i += 256) {
+  constexpr int PER_SLICE = TB * TB / 4 / TAIL_SLICES;
+  for (int i = (int)blockIdx.y * PER_SLICE + threadIdx.x; i < ((int)blockIdx.y + 1) * PER_SLICE; i += 256) {
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int c = 0; c < plan.split; ++c) {
       const float4 v = reinterpret_cast<const float4 *>(part + (size_t)c * TB * TB)[i];
@@ -765,7 +767,7 @@ template <bool TRANS_W, bool SCATTER_OUT, int ACT, bool STATIC4> int launch_s2s_
                      group_m, division_magic(a.a_map.o ? a.a_map.fan : 1));
   SMOE_LAUNCH_CHECK();
   if (args.tail_ws) {   // adds and stores the partial tiles of a split last round (no-op when nothing was split)
-    hipLaunchKernelGGL(s2s_tail_reduce_kernel<SCATTER_OUT>, dim3(STREAM_GRID - 1), dim3(256), 0, s, a, tiles_n, group_m,
+    hipLaunchKernelGGL(s2s_tail_reduce_kernel<SCATTER_OUT>, dim3(STREAM_GRID - 1, TAIL_SLICES), dim3(256), 0, s, a, tiles_n, group_m,
                        STREAM_GRID, STATIC4 ? 1 : 0);
     SMOE_LAUNCH_CHECK();
   }
