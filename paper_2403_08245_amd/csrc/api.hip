@@ -109,6 +109,7 @@ static int attention_args_ok(smoe_dtype dtype, int B, int T, int G, int h, int d
   if (dtype != SMOE_BF16 || d_head != 128) return SMOE_ERR_UNSUPPORTED;
   if ((long long)T * G > 0x3fffffffLL || (long long)B * T * G > 0x7fffffffLL || h > 65535 || B > 65535)
     return SMOE_ERR_UNSUPPORTED;
+  if ((((long long)T * G + 127) / 128) * h * B > 0x7fffffffLL) return SMOE_ERR_UNSUPPORTED;   // one-dimensional grids
   return SMOE_OK;
 }
 

@@ -20,6 +20,7 @@ constexpr int AKT = 32;             // keys (or query rows) per LDS tile
 constexpr int AROW = AD * 2;        // bytes per tile row
 constexpr int ATILE = AKT * AROW;   // 8 KB
 constexpr int AQ = 128;             // rows per block: 32 per wavefront
+constexpr int AST = 4;              // LDS stages of the key walk (forward, dQ): tiles j+1 .. j+AST-2 in flight while j is used
 constexpr int DKV_WAVES = 4;        // wavefronts (32 keys each) per block of the dK/dV kernel
 constexpr float NEG_BIG = -1.0e30f; // finite stand-in for -inf: exp2 of it is 0 and no inf - inf appears
 
@@ -143,11 +144,15 @@ struct AttnDims {
 __global__ void __launch_bounds__(256, 2) attn_fwd_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                        const bf16_t *__restrict__ V, bf16_t *__restrict__ O,
                                                        float *__restrict__ LSE, AttnDims d) {
-  __shared__ __attribute__((aligned(1024))) char smem[4 * ATILE];   // two stages of (K tile, V tile)
+  __shared__ __attribute__((aligned(1024))) char smem[AST * 2 * ATILE];   // stages of (K tile, V tile)
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int uwave = __builtin_amdgcn_readfirstlane(wave);
-  const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;              // long rows first
-  const int hh = blockIdx.y, b = blockIdx.z;
+  // Blocks are numbered longest key walk first across ALL (sequence, head) pairs: the hardware starts blocks
+  // in index order, so the short walks fill in behind the long ones everywhere at once (numbering each pair's
+  // tiles separately left the last pairs' long walks to start late: 1.6x the balanced makespan).
+  const int nbh = d.h * d.B, rank = (int)blockIdx.x / nbh, bh = (int)blockIdx.x - rank * nbh;
+  const int qt = (int)gridDim.x / nbh - 1 - rank;
+  const int hh = bh % d.h, b = bh / d.h;
   const int rows = d.T * d.G;                                        // slot rows of one sequence
   const int R0 = qt * AQ;
   const int r_mine = min(R0 + wave * 32 + (lane & 31), rows - 1);
@@ -174,19 +179,22 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_kernel(const bf16_t *__restri
     for (int q = 0; q < 16; ++q) acc[f][q] = 0.f;
   float m = NEG_BIG, l = 0.f;
 
-  load_tile_rows(Kb, d.ldkv, 0, d.T - 1, lds0, wave, uwave, lane);
-  load_tile_rows(Vb, d.ldkv, 0, d.T - 1, lds0 + ATILE, wave, uwave, lane);
+  // Every step requests one tile (four loads per wavefront), also past the last one (rows clamp to the
+  // sequence's last key and the tile is never read), so that one constant wait count orders the ring.
+  auto request = [&](int tile, int stage) {
+    const uint32_t dst = lds0 + stage * 2 * ATILE;
+    load_tile_rows(Kb, d.ldkv, tile * AKT, d.T - 1, dst, wave, uwave, lane);
+    load_tile_rows(Vb, d.ldkv, tile * AKT, d.T - 1, dst + ATILE, wave, uwave, lane);
+  };
+#pragma unroll
+  for (int t = 0; t < AST - 1; ++t) request(t, t);
   const FragOffsets fo = frag_offsets(lane);
-  // the loop is unrolled by the two LDS stages so that every tile address below is register + constant
+  // the loop is unrolled by the LDS stages so that every tile address below is register + constant
   auto tile_step = [&](auto stage_c, int j) {
     constexpr int STAGE = decltype(stage_c)::value;
-    wait_loads<0>();
-    __syncthreads();   // tile j has landed for everyone; everyone is done reading tile j-1
-    if (j + 1 < n_tiles) {
-      uint32_t nxt = lds0 + (1 - STAGE) * 2 * ATILE;
-      load_tile_rows(Kb, d.ldkv, (j + 1) * AKT, d.T - 1, nxt, wave, uwave, lane);
-      load_tile_rows(Vb, d.ldkv, (j + 1) * AKT, d.T - 1, nxt + ATILE, wave, uwave, lane);
-    }
+    wait_loads<(AST - 2) * 4>();
+    __syncthreads();   // tile j has landed for everyone; everyone is done reading tile j-1, whose stage is refilled
+    request(j + AST - 1, (STAGE + AST - 1) % AST);
     const int key0 = j * AKT;
     if (key0 > wave_last) return;   // wave-uniform: every key of the tile is in the future of all 32 rows
     const char *kt = smem + STAGE * 2 * ATILE;
@@ -232,10 +240,14 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_kernel(const bf16_t *__restri
       for (int s2 = 0; s2 < 2; ++s2)
         acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(vt, fo, f, s2), pb[s2], acc[f], 0, 0, 0);
   };
-  for (int j = 0; j < n_tiles; j += 2) {
+  static_assert(AST == 4, "the walk below is written out for four stages");
+  for (int j = 0; j < n_tiles; j += AST) {
     tile_step(std::integral_constant<int, 0>{}, j);
     if (j + 1 < n_tiles) tile_step(std::integral_constant<int, 1>{}, j + 1);
+    if (j + 2 < n_tiles) tile_step(std::integral_constant<int, 2>{}, j + 2);
+    if (j + 3 < n_tiles) tile_step(std::integral_constant<int, 3>{}, j + 3);
   }
+  wait_loads<0>();   // the requests past the last tile
 
   const float l_tot = l + __shfl_xor(l, 32, 64);
   const float inv = 1.0f / l_tot;
@@ -280,11 +292,12 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const bf16_t *__restri
                                                           const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
                                                           const float *__restrict__ LSE, const float *__restrict__ delta,
                                                           bf16_t *__restrict__ dQ, AttnDims d) {
-  __shared__ __attribute__((aligned(1024))) char smem[4 * ATILE];
+  __shared__ __attribute__((aligned(1024))) char smem[AST * 2 * ATILE];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int uwave = __builtin_amdgcn_readfirstlane(wave);
-  const int qt = (int)gridDim.x - 1 - (int)blockIdx.x;
-  const int hh = blockIdx.y, b = blockIdx.z;
+  const int nbh = d.h * d.B, rank = (int)blockIdx.x / nbh, bh = (int)blockIdx.x - rank * nbh;   // as in the forward
+  const int qt = (int)gridDim.x / nbh - 1 - rank;
+  const int hh = bh % d.h, b = bh / d.h;
   const int rows = d.T * d.G;
   const int R0 = qt * AQ;
   const int r_mine = min(R0 + wave * 32 + (lane & 31), rows - 1);
@@ -319,19 +332,20 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const bf16_t *__restri
 #pragma unroll
     for (int q = 0; q < 16; ++q) acc[f][q] = 0.f;
 
-  load_tile_rows(Kb, d.ldkv, 0, d.T - 1, lds0, wave, uwave, lane);
-  load_tile_rows(Vb, d.ldkv, 0, d.T - 1, lds0 + ATILE, wave, uwave, lane);
+  auto request = [&](int tile, int stage) {   // as in the forward: one tile per step, also past the end
+    const uint32_t dst = lds0 + stage * 2 * ATILE;
+    load_tile_rows(Kb, d.ldkv, tile * AKT, d.T - 1, dst, wave, uwave, lane);
+    load_tile_rows(Vb, d.ldkv, tile * AKT, d.T - 1, dst + ATILE, wave, uwave, lane);
+  };
+#pragma unroll
+  for (int t = 0; t < AST - 1; ++t) request(t, t);
   const FragOffsets fo = frag_offsets(lane);
-  // the loop is unrolled by the two LDS stages so that every tile address below is register + constant
+  // the loop is unrolled by the LDS stages so that every tile address below is register + constant
   auto tile_step = [&](auto stage_c, int j) {
     constexpr int STAGE = decltype(stage_c)::value;
-    wait_loads<0>();
+    wait_loads<(AST - 2) * 4>();
     __syncthreads();
-    if (j + 1 < n_tiles) {
-      uint32_t nxt = lds0 + (1 - STAGE) * 2 * ATILE;
-      load_tile_rows(Kb, d.ldkv, (j + 1) * AKT, d.T - 1, nxt, wave, uwave, lane);
-      load_tile_rows(Vb, d.ldkv, (j + 1) * AKT, d.T - 1, nxt + ATILE, wave, uwave, lane);
-    }
+    request(j + AST - 1, (STAGE + AST - 1) % AST);
     const int key0 = j * AKT;
     if (key0 > wave_last) return;
     const char *kt = smem + STAGE * 2 * ATILE;
@@ -361,10 +375,13 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const bf16_t *__restri
       for (int s2 = 0; s2 < 2; ++s2)
         acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(kt, fo, f, s2), db[s2], acc[f], 0, 0, 0);
   };
-  for (int j = 0; j < n_tiles; j += 2) {
+  for (int j = 0; j < n_tiles; j += AST) {
     tile_step(std::integral_constant<int, 0>{}, j);
     if (j + 1 < n_tiles) tile_step(std::integral_constant<int, 1>{}, j + 1);
+    if (j + 2 < n_tiles) tile_step(std::integral_constant<int, 2>{}, j + 2);
+    if (j + 3 < n_tiles) tile_step(std::integral_constant<int, 3>{}, j + 3);
   }
+  wait_loads<0>();   // the requests past the last tile
   if (row_valid) {
     bf16_t *orow = dQ + qrow;
 #pragma unroll
@@ -398,17 +415,20 @@ __global__ void __launch_bounds__(64 * NW, 2) attn_bwd_dkv_kernel(const bf16_t *
   __shared__ __attribute__((aligned(256))) float s_lse[2][64], s_dlt[2][64];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int uwave = __builtin_amdgcn_readfirstlane(wave);
-  const int hh = blockIdx.y, b = blockIdx.z;
+  // units are numbered first key block (longest row list) first, the (sequence, head) pair innermost, so that
+  // every pair's long units start together and the short ones fill in behind them
+  const int nbh = d.h * d.B, unit = (int)blockIdx.x / nbh, bh = (int)blockIdx.x - unit * nbh;
+  const int hh = bh % d.h, b = bh / d.h;
   const int rows = d.T * d.G;
   const int row_tiles = (rows + AKT - 1) / AKT;
   // work unit -> (key block, chunk of its row tiles)
   int kb = 0, unit0 = 0, nch = dkv_chunks(0, 32 * NW, d.G, row_tiles, plan.ch);
-  while (unit0 + nch <= (int)blockIdx.x) {
+  while (unit0 + nch <= unit) {
     unit0 += nch;
     ++kb;
     nch = dkv_chunks(kb, 32 * NW, d.G, row_tiles, plan.ch);
   }
-  const int chunk = (int)blockIdx.x - unit0;
+  const int chunk = unit - unit0;
   const int k0 = kb * 32 * NW;
   const int key = min(k0 + wave * 32 + (lane & 31), d.T - 1);
   const bool key_valid = k0 + wave * 32 + (lane & 31) < d.T;
@@ -519,7 +539,7 @@ __global__ void __launch_bounds__(64 * NW, 2) attn_bwd_dkv_kernel(const bf16_t *
     if (j + 1 < n_tiles) tile_step(std::integral_constant<int, 1>{}, j + 1);
   }
   if (nch > 1) {   // partial sums of this chunk: [unit][dK | dV][key][128] fp32
-    float *pk = part + ((((size_t)b * d.h + hh) * plan.units + blockIdx.x) * 2) * (32 * NW) * AD +
+    float *pk = part + ((((size_t)b * d.h + hh) * plan.units + unit) * 2) * (32 * NW) * AD +
                 (size_t)(wave * 32 + (lane & 31)) * AD;
     float *pv = pk + (size_t)(32 * NW) * AD;
 #pragma unroll
@@ -581,25 +601,35 @@ int launch_attn_fwd(hipStream_t s, const void *Q, const void *K, const void *V, 
                     int h) {
   AttnDims d{B, T, G, h, (size_t)h * AD, (size_t)h * AD, 1.4426950408889634f / sqrtf((float)AD)};
   int q_tiles = ceil_div(T * G, AQ);
-  hipLaunchKernelGGL(attn_fwd_kernel, dim3(q_tiles, h, B), dim3(256), 0, s, (const bf16_t *)Q, (const bf16_t *)K,
+  hipLaunchKernelGGL(attn_fwd_kernel, dim3(q_tiles * h * B), dim3(256), 0, s, (const bf16_t *)Q, (const bf16_t *)K,
                      (const bf16_t *)V, (bf16_t *)O, LSE, d);
   SMOE_LAUNCH_CHECK();
   return SMOE_OK;
 }
 
-static DkvPlan dkv_plan(int T, int G) {
+// The row list of a key block is cut into chunks only when that is needed to fill the chip: with enough
+// (sequence, head) pairs the whole lists, longest first, already pack to within a few percent of the balanced
+// makespan, and whole lists leave no partial sums behind.
+static DkvPlan dkv_plan(int T, int G, int nbh) {
   const int row_tiles = ceil_div(T * G, AKT), keys = 32 * DKV_WAVES;
   DkvPlan p;
-  p.ch = row_tiles / 8 > 16 ? ceil_div(row_tiles, 8) : 16;   // the longest row list splits into about eight units
   p.kblocks = ceil_div(T, keys);
+  long long tiles = 0;                       // row tiles over all key blocks of one pair
+  for (int kb = 0; kb < p.kblocks; ++kb) tiles += row_tiles - dkv_first_tile(kb, keys, G);
+  const long long balanced = tiles * nbh / 512;   // per resident block: two per compute unit
+  if ((long long)row_tiles * 20 <= balanced * 21)
+    p.ch = row_tiles;
+  else
+    p.ch = row_tiles / 8 > 16 ? ceil_div(row_tiles, 8) : 16;   // the longest row list splits into about eight units
   p.units = 0;
   for (int kb = 0; kb < p.kblocks; ++kb) p.units += dkv_chunks(kb, keys, G, row_tiles, p.ch);
   return p;
 }
 
 size_t attn_bwd_workspace_bytes(int B, int T, int G, int h) {
-  DkvPlan p = dkv_plan(T, G);
+  DkvPlan p = dkv_plan(T, G, B * h);
   size_t delta = ((size_t)B * T * G * h * sizeof(float) + 255) & ~(size_t)255;
+  if (p.ch >= ceil_div(T * G, AKT)) return delta;   // whole row lists: no partial sums
   return delta + (size_t)B * h * p.units * 2 * (32 * DKV_WAVES) * AD * sizeof(float);
 }
 
@@ -609,20 +639,23 @@ int launch_attn_bwd(hipStream_t s, const void *Q, const void *K, const void *V, 
   size_t n = (size_t)B * T * G * h;
   float *delta = (float *)ws;
   float *part = (float *)((char *)ws + ((n * sizeof(float) + 255) & ~(size_t)255));
+  constexpr int NW = DKV_WAVES;
+  const DkvPlan plan = dkv_plan(T, G, B * h);
+  if ((long long)plan.units * h * B > 0x7fffffffLL) return SMOE_ERR_UNSUPPORTED;
   hipLaunchKernelGGL(attn_delta_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, s, (const bf16_t *)O, (const bf16_t *)dO,
                      delta, n);
   SMOE_LAUNCH_CHECK();
-  hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(ceil_div(T * G, AQ), h, B), dim3(256), 0, s, (const bf16_t *)Q,
+  hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(ceil_div(T * G, AQ) * h * B), dim3(256), 0, s, (const bf16_t *)Q,
                      (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)dO, LSE, (const float *)delta, (bf16_t *)dQ, d);
   SMOE_LAUNCH_CHECK();
-  constexpr int NW = DKV_WAVES;
-  const DkvPlan plan = dkv_plan(T, G);
-  hipLaunchKernelGGL((attn_bwd_dkv_kernel<NW, true, true>), dim3(plan.units, h, B), dim3(64 * NW), 0, s, (const bf16_t *)Q,
+  hipLaunchKernelGGL((attn_bwd_dkv_kernel<NW, true, true>), dim3(plan.units * h * B), dim3(64 * NW), 0, s, (const bf16_t *)Q,
                      (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)dO, LSE, (const float *)delta, (bf16_t *)dK,
                      (bf16_t *)dV, part, plan, d);
   SMOE_LAUNCH_CHECK();
-  hipLaunchKernelGGL(attn_bwd_dkv_reduce_kernel<NW>, dim3(plan.kblocks * 8, h, B), dim3(256), 0, s, (const float *)part,
-                     (bf16_t *)dK, (bf16_t *)dV, plan, d);
-  SMOE_LAUNCH_CHECK();
+  if (plan.ch < ceil_div(T * G, AKT)) {   // some key block was cut into chunks
+    hipLaunchKernelGGL(attn_bwd_dkv_reduce_kernel<NW>, dim3(plan.kblocks * 8, h, B), dim3(256), 0, s, (const float *)part,
+                       (bf16_t *)dK, (bf16_t *)dV, plan, d);
+    SMOE_LAUNCH_CHECK();
+  }
   return SMOE_OK;
 }

@@ -120,6 +120,8 @@ PL_SHAPES = [
     (333, 72, 40, 5, 3),
     (7, 16, 24, 16, 2),
     (520, 256, 136, 3, 1),
+    (20, 64, 72, 16, 2),      # a couple of rows per expert: the forward takes the 32-row-tile kernels
+    (90, 96, 264, 3, 1),      # the same kernels with several tiles per expert and three column tiles
 ]
 
 
