@@ -20,8 +20,10 @@ constexpr int AKT = 32;             // keys (or query rows) per LDS tile
 constexpr int AROW = AD * 2;        // bytes per tile row
 constexpr int ATILE = AKT * AROW;   // 8 KB
 constexpr int AQ = 128;             // rows per block: 32 per wavefront
-constexpr int AST = 4;              // LDS stages of the key walk (forward, dQ): tiles j+1 .. j+AST-2 in flight while j is used
+constexpr int AFS = 3;              // LDS stages of the forward's key walk: tiles j+1 .. j+AFS-2 in flight while j is used; three blocks per CU
+constexpr int ADS = 4;              // the same for the dQ pass (two blocks per CU)
 constexpr int DKV_WAVES = 4;        // wavefronts (32 keys each) per block of the dK/dV kernel
+constexpr int DKV_SORT_MAX = 512;   // key blocks up to which the dK/dV units are dealt in exact longest-first order
 constexpr float NEG_BIG = -1.0e30f; // finite stand-in for -inf: exp2 of it is 0 and no inf - inf appears
 
 // 16-byte chunk swizzle of a 256-byte row: conflict free both for the row-per-lane reads
@@ -141,10 +143,10 @@ struct AttnDims {
 // ======================================================================================
 // forward: block = (query tile of 128 slot rows, head, sequence); keys stream through LDS
 // ======================================================================================
-__global__ void __launch_bounds__(256, 2) attn_fwd_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+__global__ void __launch_bounds__(256, 3) attn_fwd_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                        const bf16_t *__restrict__ V, bf16_t *__restrict__ O,
                                                        float *__restrict__ LSE, AttnDims d) {
-  __shared__ __attribute__((aligned(1024))) char smem[AST * 2 * ATILE];   // stages of (K tile, V tile)
+  __shared__ __attribute__((aligned(1024))) char smem[AFS * 2 * ATILE];   // stages of (K tile, V tile)
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int uwave = __builtin_amdgcn_readfirstlane(wave);
   // Blocks are numbered longest key walk first across ALL (sequence, head) pairs: the hardware starts blocks
@@ -187,14 +189,14 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_kernel(const bf16_t *__restri
     load_tile_rows(Vb, d.ldkv, tile * AKT, d.T - 1, dst + ATILE, wave, uwave, lane);
   };
 #pragma unroll
-  for (int t = 0; t < AST - 1; ++t) request(t, t);
+  for (int t = 0; t < AFS - 1; ++t) request(t, t);
   const FragOffsets fo = frag_offsets(lane);
   // the loop is unrolled by the LDS stages so that every tile address below is register + constant
   auto tile_step = [&](auto stage_c, int j) {
     constexpr int STAGE = decltype(stage_c)::value;
-    wait_loads<(AST - 2) * 4>();
+    wait_loads<(AFS - 2) * 4>();
     __syncthreads();   // tile j has landed for everyone; everyone is done reading tile j-1, whose stage is refilled
-    request(j + AST - 1, (STAGE + AST - 1) % AST);
+    request(j + AFS - 1, (STAGE + AFS - 1) % AFS);
     const int key0 = j * AKT;
     if (key0 > wave_last) return;   // wave-uniform: every key of the tile is in the future of all 32 rows
     const char *kt = smem + STAGE * 2 * ATILE;
@@ -240,12 +242,13 @@ __global__ void __launch_bounds__(256, 2) attn_fwd_kernel(const bf16_t *__restri
       for (int s2 = 0; s2 < 2; ++s2)
         acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(vt, fo, f, s2), pb[s2], acc[f], 0, 0, 0);
   };
-  static_assert(AST == 4, "the walk below is written out for four stages");
-  for (int j = 0; j < n_tiles; j += AST) {
+  static_assert(AFS == 3 || AFS == 4, "the walk below is written out for three or four stages");
+  for (int j = 0; j < n_tiles; j += AFS) {
     tile_step(std::integral_constant<int, 0>{}, j);
     if (j + 1 < n_tiles) tile_step(std::integral_constant<int, 1>{}, j + 1);
     if (j + 2 < n_tiles) tile_step(std::integral_constant<int, 2>{}, j + 2);
-    if (j + 3 < n_tiles) tile_step(std::integral_constant<int, 3>{}, j + 3);
+    if constexpr (AFS > 3)
+      if (j + 3 < n_tiles) tile_step(std::integral_constant<int, 3 % AFS>{}, j + 3);
   }
   wait_loads<0>();   // the requests past the last tile
 
@@ -292,7 +295,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const bf16_t *__restri
                                                           const bf16_t *__restrict__ V, const bf16_t *__restrict__ dO,
                                                           const float *__restrict__ LSE, const float *__restrict__ delta,
                                                           bf16_t *__restrict__ dQ, AttnDims d) {
-  __shared__ __attribute__((aligned(1024))) char smem[AST * 2 * ATILE];
+  __shared__ __attribute__((aligned(1024))) char smem[ADS * 2 * ATILE];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int uwave = __builtin_amdgcn_readfirstlane(wave);
   const int nbh = d.h * d.B, rank = (int)blockIdx.x / nbh, bh = (int)blockIdx.x - rank * nbh;   // as in the forward
@@ -338,14 +341,14 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const bf16_t *__restri
     load_tile_rows(Vb, d.ldkv, tile * AKT, d.T - 1, dst + ATILE, wave, uwave, lane);
   };
 #pragma unroll
-  for (int t = 0; t < AST - 1; ++t) request(t, t);
+  for (int t = 0; t < ADS - 1; ++t) request(t, t);
   const FragOffsets fo = frag_offsets(lane);
   // the loop is unrolled by the LDS stages so that every tile address below is register + constant
   auto tile_step = [&](auto stage_c, int j) {
     constexpr int STAGE = decltype(stage_c)::value;
-    wait_loads<(AST - 2) * 4>();
+    wait_loads<(ADS - 2) * 4>();
     __syncthreads();
-    request(j + AST - 1, (STAGE + AST - 1) % AST);
+    request(j + ADS - 1, (STAGE + ADS - 1) % ADS);
     const int key0 = j * AKT;
     if (key0 > wave_last) return;
     const char *kt = smem + STAGE * 2 * ATILE;
@@ -375,11 +378,12 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_kernel(const bf16_t *__restri
       for (int s2 = 0; s2 < 2; ++s2)
         acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(cols_frag(kt, fo, f, s2), db[s2], acc[f], 0, 0, 0);
   };
-  for (int j = 0; j < n_tiles; j += AST) {
+  for (int j = 0; j < n_tiles; j += ADS) {
     tile_step(std::integral_constant<int, 0>{}, j);
     if (j + 1 < n_tiles) tile_step(std::integral_constant<int, 1>{}, j + 1);
     if (j + 2 < n_tiles) tile_step(std::integral_constant<int, 2>{}, j + 2);
-    if (j + 3 < n_tiles) tile_step(std::integral_constant<int, 3>{}, j + 3);
+    if constexpr (ADS > 3)
+      if (j + 3 < n_tiles) tile_step(std::integral_constant<int, 3 % ADS>{}, j + 3);
   }
   wait_loads<0>();   // the requests past the last tile
   if (row_valid) {
@@ -421,14 +425,50 @@ __global__ void __launch_bounds__(64 * NW, 2) attn_bwd_dkv_kernel(const bf16_t *
   const int hh = bh % d.h, b = bh / d.h;
   const int rows = d.T * d.G;
   const int row_tiles = (rows + AKT - 1) / AKT;
-  // work unit -> (key block, chunk of its row tiles)
-  int kb = 0, unit0 = 0, nch = dkv_chunks(0, 32 * NW, d.G, row_tiles, plan.ch);
-  while (unit0 + nch <= unit) {
-    unit0 += nch;
-    ++kb;
-    nch = dkv_chunks(kb, 32 * NW, d.G, row_tiles, plan.ch);
+  // work unit -> (key block, chunk of its row tiles).  A key block's list is cut into full chunks of plan.ch
+  // tiles and one shorter last chunk.  Units in longest-first order: every full chunk (key blocks ascending),
+  // then the last chunks by decreasing length (ties: key block ascending) -- with the few units per resident
+  // block that a chunked launch has, short units scattered among long ones cost a fifth of the makespan.
+  // Beyond DKV_SORT_MAX key blocks the last chunks keep their natural place.
+  __shared__ int s_last[DKV_SORT_MAX];   // length of each key block's last chunk
+  __shared__ int s_pick;
+  const int KB = plan.kblocks;
+  auto chunks_of = [&](int i) { return dkv_chunks(i, 32 * NW, d.G, row_tiles, plan.ch); };
+  int kb = 0, chunk = 0;
+  if (KB > DKV_SORT_MAX || plan.ch >= row_tiles) {
+    int before = 0, c = chunks_of(0);
+    while (before + c <= unit) {
+      before += c;
+      ++kb;
+      c = chunks_of(kb);
+    }
+    chunk = unit - before;
+  } else if (unit < plan.units - KB) {
+    int before = 0, c = chunks_of(0) - 1;
+    while (before + c <= unit) {
+      before += c;
+      ++kb;
+      c = chunks_of(kb) - 1;
+    }
+    chunk = unit - before;
+  } else {
+    const int want = unit - (plan.units - KB);
+    for (int i = threadIdx.x; i < KB; i += 64 * NW)
+      s_last[i] = row_tiles - dkv_first_tile(i, 32 * NW, d.G) - (chunks_of(i) - 1) * plan.ch;
+    __syncthreads();
+    for (int i = threadIdx.x; i < KB; i += 64 * NW) {
+      const int mine = s_last[i];
+      int ahead = 0;
+      for (int o = 0; o < KB; ++o) ahead += (s_last[o] > mine) || (s_last[o] == mine && o < i);
+      if (ahead == want) s_pick = i;   // exactly one key block has this position
+    }
+    __syncthreads();
+    kb = __builtin_amdgcn_readfirstlane(s_pick);
+    chunk = chunks_of(kb) - 1;
   }
-  const int chunk = unit - unit0;
+  const int nch = chunks_of(kb);
+  int unit0 = 0;                      // units of the earlier key blocks: where this key block's partial sums start
+  for (int i = 0; i < kb; ++i) unit0 += chunks_of(i);
   const int k0 = kb * 32 * NW;
   const int key = min(k0 + wave * 32 + (lane & 31), d.T - 1);
   const bool key_valid = k0 + wave * 32 + (lane & 31) < d.T;
@@ -539,7 +579,7 @@ __global__ void __launch_bounds__(64 * NW, 2) attn_bwd_dkv_kernel(const bf16_t *
     if (j + 1 < n_tiles) tile_step(std::integral_constant<int, 1>{}, j + 1);
   }
   if (nch > 1) {   // partial sums of this chunk: [unit][dK | dV][key][128] fp32
-    float *pk = part + ((((size_t)b * d.h + hh) * plan.units + unit) * 2) * (32 * NW) * AD +
+    float *pk = part + ((((size_t)b * d.h + hh) * plan.units + unit0 + chunk) * 2) * (32 * NW) * AD +
                 (size_t)(wave * 32 + (lane & 31)) * AD;
     float *pv = pk + (size_t)(32 * NW) * AD;
 #pragma unroll
