@@ -172,6 +172,18 @@ def test_partial_last_round_split_sampled(smoe, d_model, d_expert):
         tiles = m_tiles * ((width + 255) // 256)
         assert tiles > 256 and tiles % 256 <= 64, (m_tiles, tiles)
     _run_fullsize(smoe, cfg, 12, tokens_per_expert=2, dw_samples=1, last_rows=600)
+    # the chunks' partial tiles are added in a fixed order: two runs agree bit for bit
+    case = si.mlp_case(cfg, 12)
+    gi, gg = smoe.topk_gate(case["logits"].cuda(), cfg.k)
+    r = smoe.route(gi, cfg.E)
+    X, W1, W2, dY = (case[n].cuda() for n in ("X", "W1", "W2", "dY"))
+    runs = []
+    for _ in range(2):
+        Y, buf = smoe.mlp_fwd(X, W1, W2, r, cfg.k, gg, cfg.act)
+        grads = smoe.mlp_bwd(dY, X, W1, W2, r, cfg.k, gg, cfg.act, buf)
+        runs.append([t.clone() for t in (Y,) + tuple(grads)])
+    for a, b in zip(*runs):
+        assert torch.equal(a, b)
 
 
 def test_C4_granular_sampled(smoe):
