@@ -40,3 +40,34 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in src, f"{f} mentions the oracle"
+
+
+def test_workspace_queries_are_pure_host_arithmetic():
+    """Sizes the header promises, checked without a GPU: every query is 256-byte granular, the entry points with a
+    workspace carry the 64 MiB for a split last round, and the attention backward keeps no partial sums when there
+    are enough (sequence, head) pairs to fill the chip with whole row lists."""
+    import paper_2403_08245_amd as m
+    lib, MiB = m.lib, 1 << 20
+    BF16, F32, SWIGLU, GELU = 1, 0, 2, 1
+    T, k, d_model, d_expert = 1024, 2, 512, 768
+    Tk = T * k
+    assert lib.smoe_mlp_fwd_workspace_bytes(BF16, SWIGLU, T, k, d_model, d_expert, 1) == 64 * MiB
+    inf = lib.smoe_mlp_fwd_workspace_bytes(BF16, SWIGLU, T, k, d_model, d_expert, 0)
+    assert inf == 64 * MiB + 2 * Tk * (2 * d_expert + d_expert + d_model)
+    bwd = lib.smoe_mlp_bwd_workspace_bytes(BF16, GELU, T, k, d_model, d_expert)
+    assert bwd == 64 * MiB + 2 * Tk * (d_model + d_expert + d_expert)
+    assert lib.smoe_mlp_bwd_workspace_bytes(F32, GELU, T, k, d_model, d_expert) == 64 * MiB + 4 * Tk * (d_model + 2 * d_expert)
+    # ParallelLinear backward: a grouped copy of dY and of X only for the side that arrives scattered
+    both = lib.smoe_plinear_bwd_workspace_bytes(BF16, T, d_model, d_expert, Tk, k, 0, 0, 0)
+    none = lib.smoe_plinear_bwd_workspace_bytes(BF16, Tk, d_model, d_expert, Tk, 1, 0, 1, 1)
+    assert none == 64 * MiB and both == 64 * MiB + 2 * Tk * (d_model + d_expert)
+    for q in (inf, bwd, both, lib.smoe_route_workspace_bytes(T, k, 8), lib.smoe_attention_bwd_workspace_bytes(2, 4096, 4, 4)):
+        assert q % 256 == 0
+    # invalid shapes give 0
+    assert lib.smoe_mlp_fwd_workspace_bytes(7, SWIGLU, T, k, d_model, d_expert, 1) == 0
+    assert lib.smoe_attention_bwd_workspace_bytes(0, 16, 1, 1) == 0
+    # attention backward: delta [B, T, G, h] fp32 always; partial sums only when row lists are cut into chunks
+    few = lib.smoe_attention_bwd_workspace_bytes(2, 4096, 4, 4)      # 8 pairs: chunked
+    many = lib.smoe_attention_bwd_workspace_bytes(16, 2048, 4, 8)    # 128 pairs: whole lists
+    assert many == 16 * 2048 * 4 * 8 * 4
+    assert few > 2 * 4096 * 4 * 4 * 4
