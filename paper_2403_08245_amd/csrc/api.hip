@@ -260,6 +260,7 @@ int smoe_plinear_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *
       Xg = xbar;
     }
     DWArgs a{Xg, dYbar, dW, r->expert_offsets, r->E, Tk, d_in, d_out};
+    a.split_ws = (float *)((char *)ws + need - S2S_TAIL_WS_BYTES);   // the input-gradient product below uses it afterwards
     rc = run_dw(ctx, s, dtype, a);
     if (rc != SMOE_OK) return rc;
   }
@@ -392,6 +393,7 @@ int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
   rc = launch_group(s, dtype, dY, r->sorted_scattered_idxs, k, gates, dYbar, Tk, d_model);  // weight and group
   if (rc != SMOE_OK) return rc;
   DWArgs w2{saved_H, dYbar, dW2, r->expert_offsets, r->E, Tk, d_expert, d_model};
+  w2.split_ws = tail_ws;
   rc = run_dw(ctx, s, dtype, w2);                                                      // groupXTY
   if (rc != SMOE_OK) return rc;
   S2SArgs x2 = make_s2s(dYbar, W2, dH, r, d_expert, d_model, true, true, 1, true);      // dH = dYbar W2^T
@@ -405,6 +407,7 @@ int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
   rc = launch_group(s, dtype, X, r->sorted_scattered_idxs, k, nullptr, Xbar, Tk, d_model);
   if (rc != SMOE_OK) return rc;
   DWArgs w1{Xbar, dHpre, dW1, r->expert_offsets, r->E, Tk, d_model, d_h};
+  w1.split_ws = tail_ws;
   rc = run_dw(ctx, s, dtype, w1);
   if (rc != SMOE_OK) return rc;
   if (k == 1) {  // slot id == token id: scatter straight into dX
@@ -548,6 +551,7 @@ int smoe_momha_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *dO
   if (rc != SMOE_OK) return rc;
   // dense key / value projections
   DWArgs wk{X, dK, dW_K, dense_off, 1, N, d_model, d_out}, wv{X, dV, dW_V, dense_off, 1, N, d_model, d_out};
+  wk.split_ws = wv.split_ws = (float *)((char *)sub + z.yhat + z.q);
   rc = run_dw(ctx, s, dtype, wk);
   if (rc != SMOE_OK) return rc;
   rc = run_dw(ctx, s, dtype, wv);

@@ -92,6 +92,10 @@ struct DWArgs {       // dW[e] = sum_{i in segment e} A[i, :]^T B[i, :]   (both 
   void *dW;           // [E, M, N]
   const int32_t *offsets;
   int E, Tk, M, N;
+  // Optional scratch (S2S_TAIL_WS_BYTES of device memory, or NULL): when the output tiles of all experts fill
+  // only a fraction of the chip (a dense projection run as one expert), each segment's rows are cut into chunks
+  // that leave fp32 partial tiles here, added in chunk order by a second kernel.
+  float *split_ws = nullptr;
 };
 int launch_s2s_plain(hipStream_t s, smoe_dtype dt, const S2SArgs &a);
 int launch_dw_plain(hipStream_t s, smoe_dtype dt, const DWArgs &a);

@@ -587,7 +587,25 @@ struct DWStreamOps {
   __device__ __forceinline__ bf16x8 frag_b(const char *tile, int base, int kk, int l) { return tr_frag(tile, base, kk, l); }
 };
 
-__global__ void __launch_bounds__(NTHREADS, 1) dw_stream_kernel(DWArgs a, int tiles_m, int tiles_n) {
+// tile number inside an expert -> first row and column of the tile: bands of group_m M-tiles, N-tile by
+// N-tile, so that the 32 consecutive tiles an XCD holds at a time form a compact patch sharing few panels
+__device__ __forceinline__ void dw_tile_origin(int t, int tiles_m, int tiles_n, int &m0, int &n0) {
+  const int group_m = (tiles_m % 8 == 0) ? 8 : ((tiles_m % 4 == 0) ? 4 : ((tiles_m % 2 == 0) ? 2 : 1));
+  const int band = t / (group_m * tiles_n), r = t - band * (group_m * tiles_n);
+  m0 = (band * group_m + r % group_m) * TB;
+  n0 = (r / group_m) * TB;
+}
+// rows of chunk `chunk` of `split` of the segment [lo, hi): chunks are whole groups of four half-steps
+__device__ __forceinline__ void dw_chunk_rows(int lo, int hi, int split, int chunk, int &clo, int &chi) {
+  const int nh = (hi - lo + HK - 1) / HK;
+  const int len = (((nh + split - 1) / split + 3) & ~3) * HK;
+  clo = min(hi, lo + chunk * len);
+  chi = min(hi, clo + len);
+}
+
+// split > 1 (only when all experts' tiles times split fit one round of the grid): unit T is chunk T % split of
+// tile T / split, experts in their own order, and the result is an fp32 partial tile number T in a.split_ws.
+__global__ void __launch_bounds__(NTHREADS, 1) dw_stream_kernel(DWArgs a, int tiles_m, int tiles_n, int split) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   __shared__ int s_off[MAX_E + 1];
   __shared__ int s_order[MAX_E];      // experts, largest segment first
@@ -597,7 +615,6 @@ __global__ void __launch_bounds__(NTHREADS, 1) dw_stream_kernel(DWArgs a, int ti
   const int G = gridDim.x;
   const int slot_in_round = ((int)blockIdx.x & 7) * (G >> 3) + ((int)blockIdx.x >> 3);  // XCD-contiguous tiles
   const int per_expert = tiles_m * tiles_n;
-  const int group_m = (tiles_m % 8 == 0) ? 8 : ((tiles_m % 4 == 0) ? 4 : ((tiles_m % 2 == 0) ? 2 : 1));
 
   for (int i = threadIdx.x; i <= a.E; i += NTHREADS) s_off[i] = a.offsets[i];
   __syncthreads();
@@ -613,19 +630,17 @@ __global__ void __launch_bounds__(NTHREADS, 1) dw_stream_kernel(DWArgs a, int ti
 
   auto open_tile = [&](DWCursor &c, int seq) {
     c.seq = seq;
-    int T = seq * G + slot_in_round;
+    const int U = seq * G + slot_in_round;
+    const int T = U / split;
     int rank = T / per_expert;
-    c.live = rank < a.E;
+    c.live = rank < a.E && (split == 1 || seq == 0);
     if (!c.live) return;
     int t = T - rank * per_expert;
-    c.e = __builtin_amdgcn_readfirstlane(s_order[rank]);   // LDS reads land in vector registers: make them scalar again
+    c.e = split > 1 ? rank : __builtin_amdgcn_readfirstlane(s_order[rank]);   // LDS reads land in vector registers: make them scalar again
     c.lo = __builtin_amdgcn_readfirstlane(s_off[c.e]);
     c.hi = __builtin_amdgcn_readfirstlane(s_off[c.e + 1]);
-    // inside an expert: bands of group_m M-tiles, N-tile by N-tile, so that the 32 consecutive
-    // tiles an XCD holds at a time form a compact patch sharing few operand panels
-    int band = t / (group_m * tiles_n), r = t - band * (group_m * tiles_n);
-    c.m0 = (band * group_m + r % group_m) * TB;
-    c.n0 = (r / group_m) * TB;
+    if (split > 1) dw_chunk_rows(c.lo, c.hi, split, U - T * split, c.lo, c.hi);
+    dw_tile_origin(t, tiles_m, tiles_n, c.m0, c.n0);
     c.nh = (c.hi - c.lo + HK - 1) / HK;
     // Slots come in groups of four so that every tile starts in LDS stage 0 and the loop can be written
     // with compile-time stages; the up to three extra slots (four for an empty expert) load the zero
@@ -732,12 +747,39 @@ __global__ void __launch_bounds__(NTHREADS, 1) dw_stream_kernel(DWArgs a, int ti
     open_slot();   // the next tile's first slot, before the stores below join the load counter
     const int mbase = cc.m0 + wm * (TB / 2);
     auto dst_row = [&](int r) -> int { return (mbase + r < a.M) ? mbase + r : -1; };
-    store_wave_tile(acc, patch, dst_row, (bf16_t *)a.dW + (size_t)cc.e * a.M * a.N, a.N, cc.n0 + wn * (TB / 2), a.N,
-                    lane);
+    if (split > 1)
+      store_wave_partial(acc, a.split_ws + (size_t)(cc.seq * G + slot_in_round) * TB * TB + (size_t)(wm * (TB / 2)) * TB + wn * (TB / 2), lane);
+    else
+      store_wave_tile(acc, patch, dst_row, (bf16_t *)a.dW + (size_t)cc.e * a.M * a.N, a.N, cc.n0 + wn * (TB / 2), a.N,
+                      lane);
     open_tile(cc, cc.seq + 1);
     if (!cc.live) break;
   }
   wait_loads<0>();
+}
+
+// Second pass of a row-split groupXTY: adds each tile's partials in chunk order, rounds once, stores dW.
+__global__ void __launch_bounds__(256) dw_split_reduce_kernel(DWArgs a, int tiles_m, int tiles_n, int split) {
+  const int per_expert = tiles_m * tiles_n;
+  const int T = blockIdx.x, e = T / per_expert;
+  int m0, n0;
+  dw_tile_origin(T - e * per_expert, tiles_m, tiles_n, m0, n0);
+  const float *part = a.split_ws + (size_t)T * split * TB * TB;
+  bf16_t *dW = (bf16_t *)a.dW + (size_t)e * a.M * a.N;
+  constexpr int PER_SLICE = TB * TB / 4 / TAIL_SLICES;
+  for (int i = (int)blockIdx.y * PER_SLICE + threadIdx.x; i < ((int)blockIdx.y + 1) * PER_SLICE; i += 256) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int c = 0; c < split; ++c) {
+      const float4 v = reinterpret_cast<const float4 *>(part + (size_t)c * TB * TB)[i];
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    const int row = m0 + (i * 4) / TB, col = n0 + (i * 4) % TB;
+    if (row < a.M && col < a.N) {
+      bf16x4 o;
+      o[0] = (bf16_t)acc.x; o[1] = (bf16_t)acc.y; o[2] = (bf16_t)acc.z; o[3] = (bf16_t)acc.w;
+      *reinterpret_cast<bf16x4 *>(dW + (size_t)row * a.N + col) = o;
+    }
+  }
 }
 
 template <typename K> int set_lds_limit(K kernel, int bytes) {
@@ -778,8 +820,21 @@ int launch_dw_stream_impl(hipStream_t s, const DWArgs &a) {
   static int attr_rc = set_lds_limit(dw_stream_kernel, STREAM_LDS_BYTES);
   if (attr_rc != SMOE_OK) return attr_rc;
   int tiles_m = ceil_div(a.M, TB), tiles_n = ceil_div(a.N, TB);
-  hipLaunchKernelGGL(dw_stream_kernel, dim3(STREAM_GRID), dim3(NTHREADS), STREAM_LDS_BYTES, s, a, tiles_m, tiles_n);
+  // Row split: only when every tile of every expert, times the split, fits one round of the grid, and only when
+  // it shortens the contraction by more than the partial tiles cost (as for the split last round above).
+  int split = 1;
+  const long long tiles = (long long)a.E * tiles_m * tiles_n;
+  if (a.split_ws && tiles * 2 <= STREAM_GRID) {
+    const long long nh = a.Tk / a.E / HK;            // half-steps of an average segment
+    split = (int)(STREAM_GRID / tiles < 8 ? STREAM_GRID / tiles : 8);
+    if (nh - nh / split < SPLIT_MIN_SAVED) split = 1;
+  }
+  hipLaunchKernelGGL(dw_stream_kernel, dim3(STREAM_GRID), dim3(NTHREADS), STREAM_LDS_BYTES, s, a, tiles_m, tiles_n, split);
   SMOE_LAUNCH_CHECK();
+  if (split > 1) {
+    hipLaunchKernelGGL(dw_split_reduce_kernel, dim3((unsigned)tiles, TAIL_SLICES), dim3(256), 0, s, a, tiles_m, tiles_n, split);
+    SMOE_LAUNCH_CHECK();
+  }
   return SMOE_OK;
 }
 }  // namespace

@@ -150,6 +150,27 @@ def test_plinear_forward_and_backward(smoe, shape, gin, gout, with_p, dtype):
         assert_close(dg, dp_ref, td, "dgates")
 
 
+@pytest.mark.parametrize("E,gin,gout,with_p", [(2, 0, 0, 1), (1, 1, 1, 0), (3, 0, 1, 0)])
+def test_plinear_weight_gradient_with_few_tiles_and_many_rows(smoe, E, gin, gout, with_p):
+    """A handful of output tiles per expert and thousands of rows: the weight gradient cuts every expert's rows
+    into chunks (fp32 partial tiles, added in chunk order by a second kernel) so that the chip is not left idle;
+    the third case has a width that is not a multiple of the tile."""
+    T, d_in, d_out, k = 8192, 256, 264 if E == 3 else 256, 1
+    td = torch.bfloat16
+    c, (ei, g, se, o, off), (gi, gg, r) = _plinear_setup(smoe, T, d_in, d_out, E, k, "bf16", 21, gin)
+    X, W = si.as_f64(c["X"]), si.as_f64(c["W"])
+    p64 = gg.cpu().numpy().astype(np.float64) if with_p else None
+    Y, Yhat = smoe.plinear_fwd(c["X"].cuda(), c["W"].cuda(), r, k, gg if with_p else None, bool(gin), bool(gout))
+    dY_t = c["dY_T"] if with_p else c["dY_Tk"]
+    dX_ref, dW_ref, dp_ref = oracle.plinear_bwd(si.as_f64(dY_t), X, W, se, o, k, p64, bool(gin), bool(gout))
+    outs = [smoe.plinear_bwd(dY_t.cuda(), c["X"].cuda(), c["W"].cuda(), Yhat, r, k, gg if with_p else None, bool(gin), bool(gout))
+            for _ in range(2)]
+    dX, dW, dg = outs[0]
+    assert_close(dW, dW_ref, td, "dW")
+    assert_close(dX, dX_ref, td, "dX")
+    assert torch.equal(outs[0][1], outs[1][1])       # fixed summation order
+
+
 def test_group_matches_definition(smoe):
     c, (ei, g, se, o, off), (gi, gg, r) = _plinear_setup(smoe, 200, 64, 64, 6, 2, "bf16", 3, 0)
     out = smoe.group(c["X"].cuda(), r, 2)
