@@ -272,18 +272,23 @@ __global__ void __launch_bounds__(256, 3) attn_fwd_kernel(const bf16_t *__restri
 
 
 // ======================================================================================
-// backward, part 0: delta[row][head] = <dO, O> over the head's 128 columns (one wavefront each)
+// backward, part 0: delta[row][head] = <dO, O> over the head's 128 columns (sixteen lanes each)
 // ======================================================================================
 __global__ void __launch_bounds__(256) attn_delta_kernel(const bf16_t *__restrict__ O, const bf16_t *__restrict__ dO,
                                                          float *__restrict__ delta, size_t n) {
-  size_t i = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // (row, head) pair; both tensors are [rows][h][128]
-  if (i >= n) return;
-  const int lane = threadIdx.x & 63;
-  const bf16_t *a = O + i * AD + lane * 2, *b = dO + i * AD + lane * 2;
-  float v = (float)a[0] * (float)b[0] + (float)a[1] * (float)b[1];
+  // sixteen lanes per (row, head) pair, 16 bytes each; both tensors are [rows][h][128]
+  const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) >> 4;
+  const int part = threadIdx.x & 15;
+  float v = 0.f;
+  if (i < n) {
+    const bf16x8 a = *reinterpret_cast<const bf16x8 *>(O + i * AD + part * 8);
+    const bf16x8 b = *reinterpret_cast<const bf16x8 *>(dO + i * AD + part * 8);
 #pragma unroll
-  for (int d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d, 64);
-  if (lane == 0) delta[i] = v;
+    for (int c = 0; c < 8; ++c) v += (float)a[c] * (float)b[c];
+  }
+#pragma unroll
+  for (int d = 8; d > 0; d >>= 1) v += __shfl_xor(v, d, 64);
+  if (part == 0 && i < n) delta[i] = v;
 }
 
 // ======================================================================================
@@ -682,7 +687,7 @@ int launch_attn_bwd(hipStream_t s, const void *Q, const void *K, const void *V, 
   constexpr int NW = DKV_WAVES;
   const DkvPlan plan = dkv_plan(T, G, B * h);
   if ((long long)plan.units * h * B > 0x7fffffffLL) return SMOE_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(attn_delta_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, s, (const bf16_t *)O, (const bf16_t *)dO,
+  hipLaunchKernelGGL(attn_delta_kernel, dim3((unsigned)((n + 15) / 16)), dim3(256), 0, s, (const bf16_t *)O, (const bf16_t *)dO,
                      delta, n);
   SMOE_LAUNCH_CHECK();
   hipLaunchKernelGGL(attn_bwd_dq_kernel, dim3(ceil_div(T * G, AQ) * h * B), dim3(256), 0, s, (const bf16_t *)Q,
