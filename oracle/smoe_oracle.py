@@ -106,7 +106,9 @@ def topk_gate(logits: np.ndarray, k: int):
 
     Returns (expert_idxs [T,k] int32, gates [T,k] float64).  Slots are ordered
     by descending logit, ties to the lower expert id; the gates are the softmax
-    over the k kept logits.
+    over the k kept logits.  The paper is silent on non-finite logits; reading:
+    a NaN logit counts as -inf, and kept logits that are all -inf share the
+    weight equally (the limit of equal logits).
     """
     logits = np.asarray(logits)
     T, E = logits.shape
@@ -116,9 +118,10 @@ def topk_gate(logits: np.ndarray, k: int):
     gates = np.empty((T, k), dtype=np.float64)
     for t in range(T):
         row = logits[t].astype(np.float64)
+        row[np.isnan(row)] = -np.inf
         order = np.argsort(-row, kind="stable")      # descending, ties keep lower id first
         top = order[:k]
-        z = row[top] - row[top[0]]
+        z = row[top] - row[top[0]] if row[top[0]] > -np.inf else np.zeros(k)
         w = np.exp(z)
         expert_idxs[t] = top
         gates[t] = w / w.sum()

@@ -510,3 +510,23 @@ def test_pins_catch_planted_mistakes(golden_dir, monkeypatch):
     good, _ = so.plinear_fwd(X, W, se, o, 2)
     bad, _ = so.plinear_fwd(np.repeat(X, 2, 0)[::-1].copy(), W, se, o, 1)
     assert not np.allclose(good, bad)
+
+
+# ---------------------------------------------------------------- non-finite router logits (reading, Sec. 3.1 step 1)
+NONFINITE_LOGITS = np.array([[np.nan, 1.0, -np.inf, 2.0],       # 2, 1, then the NaN (as -inf) before the real -inf: lower id
+                             [np.nan, np.nan, np.nan, np.nan],  # nothing to choose from: ids in order, equal weights
+                             [-np.inf, np.nan, 0.0, -np.inf],   # one number, then -inf ties by id
+                             [3.0, np.nan, 3.0, 1.0]], dtype=np.float32)
+NONFINITE_IDX = [[3, 1, 0], [0, 1, 2], [2, 0, 1], [0, 2, 3]]
+E1 = float(np.e)
+NONFINITE_GATES = [[E1 / (1 + E1), 1 / (1 + E1), 0.0], [1 / 3, 1 / 3, 1 / 3], [1.0, 0.0, 0.0],
+                   [1 / (2 + np.exp(-2.0)), 1 / (2 + np.exp(-2.0)), np.exp(-2.0) / (2 + np.exp(-2.0))]]
+
+
+def test_topk_gate_with_nan_and_infinite_logits():
+    """The paper does not say what a NaN logit means.  Reading: NaN counts as -inf; kept logits that are all
+    -inf share the weight equally.  Expected values worked out by hand (softmax of 2, 1, -inf is e/(1+e), 1/(1+e), 0)."""
+    ei, g = oracle.topk_gate(NONFINITE_LOGITS, 3)
+    assert ei.tolist() == NONFINITE_IDX
+    np.testing.assert_allclose(g, NONFINITE_GATES, atol=1e-15)
+    assert np.isfinite(g).all() and np.allclose(g.sum(1), 1.0)
