@@ -17,8 +17,11 @@
  *   - `ws` / `ws_bytes`: scratch device memory supplied by the caller, at least as large
  *     as the matching *_workspace_bytes() query, 256-byte aligned.  Contents are
  *     unspecified on entry and on return.
- *   - Return value: SMOE_OK (0) or a negative smoe_status.  On error nothing has been
- *     enqueued.  No entry point throws or aborts.  Index *contents* (expert ids in
+ *   - Return value: SMOE_OK (0) or a negative smoe_status.  Argument, shape and workspace
+ *     errors (INVALID_ARG, UNSUPPORTED, WORKSPACE) are found before anything is enqueued.
+ *     SMOE_ERR_HIP reports a kernel launch the runtime refused: launches made earlier in
+ *     the same call stay enqueued and the call's outputs are then unspecified.
+ *     No entry point throws or aborts.  Index *contents* (expert ids in
  *     [0,E), a valid permutation in sorted_scattered_idxs) are the caller's contract:
  *     they live on the device and are not validated; out-of-range expert ids passed to
  *     smoe_route are clamped so that no out-of-bounds access happens.
@@ -66,8 +69,10 @@ typedef struct {
 } smoe_routing;
 
 /* Creates a context for HIP device `device` (host call; queries device properties).
- * *out is owned by the caller until smoe_destroy.  One context may be used from several
- * streams; it holds no mutable state on the hot path. */
+ * Also raises, on that device, the dynamic-LDS limit of the kernels that need it, so one context
+ * per device is all a process needs.  *out is owned by the caller until smoe_destroy.  One context
+ * may be used from several streams and threads: the entry points only read it.  The one exception
+ * is smoe_set_kernel_mode below, which must not run concurrently with any other call. */
 int smoe_create(smoe_ctx **out, int device);
 void smoe_destroy(smoe_ctx *ctx);
 /* Static string for a smoe_status value. */
@@ -77,7 +82,8 @@ int smoe_abi_version(void);
 
 /* Selects the GEMM kernel family: 0 = automatic (persistent matrix-core kernels whenever the
  * shape allows), 1 = force the plain tiled kernels, 2 = matrix-core kernels with one block per
- * tile (1 and 2 are testing aids).  Host-only, not thread safe. */
+ * tile (1 and 2 are testing aids).  Host-only; writes the context, so no other call on the same
+ * context may be in progress. */
 int smoe_set_kernel_mode(smoe_ctx *ctx, int mode);
 
 /* ---- routing: Sec. 3.1 step 1 -------------------------------------------------------
@@ -85,7 +91,8 @@ int smoe_set_kernel_mode(smoe_ctx *ctx, int mode);
  * id, slots ordered by descending logit) and the softmax over those k logits.
  *   logits      [T,E] fp32 (in)
  *   expert_idxs [T*k] int32 (out), gates [T*k] fp32 (out), both in slot order t*k+j.
- * Needs 1 <= k <= E.  T = 0 is a no-op. */
+ * Needs 1 <= k <= E.  T = 0 is a no-op.  A NaN logit counts as -inf; kept logits that are all
+ * -inf share the weight equally, so every slot is always written. */
 int smoe_topk_gate(smoe_ctx *ctx, void *stream, const float *logits, int T, int E, int k,
                    int32_t *expert_idxs, float *gates);
 
@@ -100,7 +107,8 @@ int smoe_topk_gate_bwd(smoe_ctx *ctx, void *stream, const int32_t *expert_idxs, 
 
 /* ---- routing: Sec. 3.1 step 2 -------------------------------------------------------
  * Stable bucket sort of the Tk = T*k slots by expert.  Outputs as in smoe_routing.
- * Integer work, bit-exact.  Experts nobody chose get an empty segment. */
+ * Integer work, bit-exact.  Experts nobody chose get an empty segment.  E <= 16384 (one
+ * counter per expert in LDS), else SMOE_ERR_UNSUPPORTED. */
 size_t smoe_route_workspace_bytes(int T, int k, int E);
 int smoe_route(smoe_ctx *ctx, void *stream, const int32_t *expert_idxs, int T, int k, int E,
                int32_t *sorted_expert_idxs, int32_t *sorted_scattered_idxs,

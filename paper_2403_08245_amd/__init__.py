@@ -136,8 +136,18 @@ def _chk(t: torch.Tensor, dtype=None):
     return t
 
 
+def _new(*shape, dtype, device) -> torch.Tensor:
+    """Every output and scratch tensor of this binding comes from here (uninitialised device memory).
+    Tests replace this one function to poison new tensors and to put guard bands around them."""
+    return torch.empty(*shape, dtype=dtype, device=device)
+
+
+def _like(t: torch.Tensor) -> torch.Tensor:
+    return _new(*t.shape, dtype=t.dtype, device=t.device)
+
+
 def _ws(nbytes: int, device) -> torch.Tensor | None:
-    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+    return _new(max(nbytes, 256), dtype=torch.uint8, device=device)
 
 
 @dataclass
@@ -157,8 +167,8 @@ class Routing:
 def topk_gate(logits: torch.Tensor, k: int):
     _chk(logits, torch.float32)
     T, E = logits.shape
-    idx = torch.empty(T, k, dtype=torch.int32, device=logits.device)
-    gates = torch.empty(T, k, dtype=torch.float32, device=logits.device)
+    idx = _new(T, k, dtype=torch.int32, device=logits.device)
+    gates = _new(T, k, dtype=torch.float32, device=logits.device)
     _check(lib.smoe_topk_gate(ctx(), _stream(), _p(logits), T, E, k, _p(idx), _p(gates)), "smoe_topk_gate")
     return idx, gates
 
@@ -170,7 +180,7 @@ def topk_gate_bwd(expert_idxs: torch.Tensor, gates: torch.Tensor, dgates: torch.
     T, k = expert_idxs.shape
     if gates.numel() != T * k or dgates.numel() != T * k:
         raise ValueError("gates and dgates must hold T*k entries")
-    dlogits = torch.empty(T, E, dtype=torch.float32, device=gates.device)
+    dlogits = _new(T, E, dtype=torch.float32, device=gates.device)
     _check(lib.smoe_topk_gate_bwd(ctx(), _stream(), _p(expert_idxs), _p(gates), _p(dgates), T, E, k, _p(dlogits)),
            "smoe_topk_gate_bwd")
     return dlogits
@@ -183,8 +193,8 @@ def attention_fwd(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor):
     B, T, G, h, d = Q.shape
     if K.shape != (B, T, h, d) or V.shape != K.shape:
         raise ValueError("K and V must be [B, T, h, d]")
-    O = torch.empty_like(Q)
-    LSE = torch.empty(B, T, G, h, dtype=torch.float32, device=Q.device)
+    O = _like(Q)
+    LSE = _new(B, T, G, h, dtype=torch.float32, device=Q.device)
     _check(lib.smoe_attention_fwd(ctx(), _stream(), BF16, _p(Q), _p(K), _p(V), B, T, G, h, d, _p(O), _p(LSE)),
            "smoe_attention_fwd")
     return O, LSE
@@ -195,7 +205,7 @@ def attention_bwd(dO, Q, K, V, O, LSE):
         _chk(t, torch.bfloat16)
     _chk(LSE, torch.float32)
     B, T, G, h, d = Q.shape
-    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    dQ, dK, dV = _like(Q), _like(K), _like(V)
     nb = lib.smoe_attention_bwd_workspace_bytes(B, T, G, h)
     ws = _ws(nb, Q.device)
     _check(lib.smoe_attention_bwd(ctx(), _stream(), BF16, _p(dO), _p(Q), _p(K), _p(V), _p(O), _p(LSE), B, T, G, h, d,
@@ -222,10 +232,10 @@ def momha_fwd(X, W_K, W_V, W_Q, W_O, r: Routing, k: int, gates, B: int, T: int, 
     d_out = h_expert * d_head
     dev = X.device
     bf = dict(dtype=torch.bfloat16, device=dev)
-    buf = MomhaBuffers(torch.empty(N, d_out, **bf), torch.empty(N, d_out, **bf), torch.empty(N * k, d_out, **bf),
-                       torch.empty(N * k, d_out, **bf), torch.empty(N * k, h_expert, dtype=torch.float32, device=dev),
-                       torch.empty(N * k, d_model, **bf))
-    O = torch.empty(N, d_model, **bf)
+    buf = MomhaBuffers(_new(N, d_out, **bf), _new(N, d_out, **bf), _new(N * k, d_out, **bf),
+                       _new(N * k, d_out, **bf), _new(N * k, h_expert, dtype=torch.float32, device=dev),
+                       _new(N * k, d_model, **bf))
+    O = _new(N, d_model, **bf)
     nb = lib.smoe_momha_fwd_workspace_bytes(B, T, k, d_model, h_expert, d_head, 1)
     ws = _ws(nb, dev)
     rc = r.c()
@@ -239,9 +249,9 @@ def momha_bwd(dO, X, W_K, W_V, W_Q, W_O, r: Routing, k: int, gates, B: int, T: i
               buf: MomhaBuffers):
     _chk(dO, torch.bfloat16)
     N, d_model = X.shape
-    dX, dW_K, dW_V = torch.empty_like(X), torch.empty_like(W_K), torch.empty_like(W_V)
-    dW_Q, dW_O = torch.empty_like(W_Q), torch.empty_like(W_O)
-    dgates = torch.empty(N, k, dtype=torch.float32, device=X.device)
+    dX, dW_K, dW_V = _like(X), _like(W_K), _like(W_V)
+    dW_Q, dW_O = _like(W_Q), _like(W_O)
+    dgates = _new(N, k, dtype=torch.float32, device=X.device)
     nb = lib.smoe_momha_bwd_workspace_bytes(B, T, k, d_model, h_expert, d_head)
     ws = _ws(nb, X.device)
     rc = r.c()
@@ -256,9 +266,9 @@ def route(expert_idxs: torch.Tensor, E: int) -> Routing:
     _chk(expert_idxs, torch.int32)
     T, k = expert_idxs.shape
     dev = expert_idxs.device
-    se = torch.empty(T * k, dtype=torch.int32, device=dev)
-    so = torch.empty(T * k, dtype=torch.int32, device=dev)
-    off = torch.empty(E + 1, dtype=torch.int32, device=dev)
+    se = _new(T * k, dtype=torch.int32, device=dev)
+    so = _new(T * k, dtype=torch.int32, device=dev)
+    off = _new(E + 1, dtype=torch.int32, device=dev)
     nb = lib.smoe_route_workspace_bytes(T, k, E)
     ws = _ws(nb, dev)
     _check(lib.smoe_route(ctx(), _stream(), _p(expert_idxs), T, k, E, _p(se), _p(so), _p(off), _p(ws), ws.numel()),
@@ -268,7 +278,7 @@ def route(expert_idxs: torch.Tensor, E: int) -> Routing:
 
 def group(x: torch.Tensor, r: Routing, fan: int, gates: torch.Tensor | None = None) -> torch.Tensor:
     _chk(x)
-    out = torch.empty(r.Tk, x.shape[1], dtype=x.dtype, device=x.device)
+    out = _new(r.Tk, x.shape[1], dtype=x.dtype, device=x.device)
     rc = r.c()
     _check(lib.smoe_group(ctx(), _stream(), _dt(x), _p(x), x.shape[1], ctypes.byref(rc), fan,
                           _p(None if gates is None else _chk(gates, torch.float32)), _p(out)), "smoe_group")
@@ -279,12 +289,12 @@ def plinear_fwd(X, W, r: Routing, k: int, gates=None, grouped_in=False, grouped_
     """Alg. 1.  Returns (Y, Yhat); Y is Yhat when no gates are given."""
     _chk(X); _chk(W, X.dtype)
     d_in, d_out = W.shape[1], W.shape[2]
-    Yhat = torch.empty(r.Tk, d_out, dtype=X.dtype, device=X.device)
+    Yhat = _new(r.Tk, d_out, dtype=X.dtype, device=X.device)
     Y, gk = None, 0
     if gates is not None:
         _chk(gates, torch.float32)
         gk = gates.shape[1]
-        Y = torch.empty(r.Tk // gk, d_out, dtype=X.dtype, device=X.device)
+        Y = _new(r.Tk // gk, d_out, dtype=X.dtype, device=X.device)
     rc = r.c()
     _check(lib.smoe_plinear_fwd(ctx(), _stream(), _dt(X), _p(X), X.shape[0], d_in, _p(W), d_out, ctypes.byref(rc), k,
                                 _p(gates), gk, int(grouped_in), int(grouped_out), _p(Yhat), _p(Y)), "smoe_plinear_fwd")
@@ -296,13 +306,13 @@ def plinear_bwd(dY, X, W, Yhat, r: Routing, k: int, gates=None, grouped_in=False
     """Alg. 2.  Returns (dX, dW, dgates)."""
     _chk(dY, X.dtype); _chk(X); _chk(W, X.dtype)
     d_in, d_out = W.shape[1], W.shape[2]
-    dX = torch.empty_like(X) if need_dX else None
-    dW = torch.empty_like(W) if need_dW else None
+    dX = _like(X) if need_dX else None
+    dW = _like(W) if need_dW else None
     dg, gk = None, 0
     if gates is not None:
         _chk(gates, torch.float32)
         gk = gates.shape[1]
-        dg = torch.empty_like(gates)
+        dg = _like(gates)
     nb = lib.smoe_plinear_bwd_workspace_bytes(_dt(X), X.shape[0], d_in, d_out, r.Tk, k, int(gates is not None),
                                               int(grouped_in), int(grouped_out))
     ws = _ws(nb, X.device)
@@ -324,14 +334,14 @@ class MLPBuffers:
     def __init__(self, T, k, E, d_model, d_expert, act, dtype, device, training=True):
         Tk, d_h = T * k, hidden_width(act, d_expert)
         dt = F32 if dtype == torch.float32 else BF16
-        mk = lambda *s: torch.empty(*s, dtype=dtype, device=device)
+        mk = lambda *s: _new(*s, dtype=dtype, device=device)
         self.T, self.k, self.E, self.d_model, self.d_expert, self.act, self.dtype = T, k, E, d_model, d_expert, act, dtype
         self.Y = mk(T, d_model)
         self.training = training
         if training:
             self.Hpre, self.H, self.Yhat = mk(Tk, d_h), mk(Tk, d_expert), mk(Tk, d_model)
             self.dX, self.dW1, self.dW2 = mk(T, d_model), mk(E, d_model, d_h), mk(E, d_expert, d_model)
-            self.dgates = torch.empty(T, k, dtype=torch.float32, device=device)
+            self.dgates = _new(T, k, dtype=torch.float32, device=device)
             self.ws_bwd = _ws(lib.smoe_mlp_bwd_workspace_bytes(dt, act, T, k, d_model, d_expert), device)
         else:
             self.Hpre = self.H = self.Yhat = None

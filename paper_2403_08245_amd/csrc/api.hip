@@ -15,15 +15,17 @@ bool routing_ok(const smoe_routing *r) {
 bool width_ok(smoe_dtype dt, int d) { return d > 0 && d % (int)(16 / dtype_size(dt)) == 0; }
 bool dtype_ok(int dt) { return dt == SMOE_F32 || dt == SMOE_BF16; }
 
-int run_s2s(smoe_ctx *ctx, hipStream_t s, smoe_dtype dt, const S2SArgs &a) {
+int run_s2s(smoe_ctx *ctx, hipStream_t s, smoe_dtype dt, S2SArgs a) {
+  a.grid = ctx->stream_grid;
   if (dt == SMOE_BF16 && ctx->kernel_mode == 0 && s2s_decode_supported(a)) return launch_s2s_decode(s, a);
   if (dt == SMOE_BF16 && ctx->kernel_mode == 0 && s2s_stream_supported(a)) return launch_s2s_stream(s, a);
-  if (dt == SMOE_BF16 && ctx->kernel_mode != 1 && s2s_mfma_supported(a)) return launch_s2s_mfma(s, a, ctx->num_cu);
+  if (dt == SMOE_BF16 && ctx->kernel_mode != 1 && s2s_mfma_supported(a)) return launch_s2s_mfma(s, a);
   return launch_s2s_plain(s, dt, a);
 }
-int run_dw(smoe_ctx *ctx, hipStream_t s, smoe_dtype dt, const DWArgs &a) {
+int run_dw(smoe_ctx *ctx, hipStream_t s, smoe_dtype dt, DWArgs a) {
+  a.grid = ctx->stream_grid;
   if (dt == SMOE_BF16 && ctx->kernel_mode == 0 && dw_stream_supported(a)) return launch_dw_stream(s, a);
-  if (dt == SMOE_BF16 && ctx->kernel_mode != 1 && dw_mfma_supported(a)) return launch_dw_mfma(s, a, ctx->num_cu);
+  if (dt == SMOE_BF16 && ctx->kernel_mode != 1 && dw_mfma_supported(a)) return launch_dw_mfma(s, a);
   return launch_dw_plain(s, dt, a);
 }
 
@@ -73,7 +75,21 @@ int smoe_create(smoe_ctx **out, int device) {
   if (!c) return SMOE_ERR_HIP;
   c->device = device;
   c->num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+  // persistent kernels: one block per compute unit, dealt to the XCDs in eight equal shares
+  c->stream_grid = c->num_cu >= 256 ? 256 : (c->num_cu & ~7);
   c->kernel_mode = 0;
+  // kernel attributes are per device: set them with this context's device current, then restore the caller's
+  int prev = -1;
+  int rc = SMOE_ERR_HIP;
+  if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(device) == hipSuccess) {
+    rc = init_stream_kernels();
+    if (rc == SMOE_OK) rc = init_mfma_kernels();
+    if (hipSetDevice(prev) != hipSuccess && rc == SMOE_OK) rc = SMOE_ERR_HIP;
+  }
+  if (rc != SMOE_OK) {
+    delete c;
+    return rc;
+  }
   *out = c;
   return SMOE_OK;
 }
@@ -145,7 +161,7 @@ int smoe_route(smoe_ctx *ctx, void *stream, const int32_t *expert_idxs, int T, i
                int32_t *sorted_expert_idxs, int32_t *sorted_scattered_idxs, int32_t *expert_offsets, void *ws,
                size_t ws_bytes) {
   if (!ctx || T < 0 || k < 1 || E < 1 || !expert_offsets) return SMOE_ERR_INVALID_ARG;
-  if ((long long)T * k > 0x7fffffffLL) return SMOE_ERR_UNSUPPORTED;
+  if ((long long)T * k > 0x7fffffffLL || E > ROUTE_MAX_E) return SMOE_ERR_UNSUPPORTED;
   if (T > 0 && (!expert_idxs || !sorted_expert_idxs || !sorted_scattered_idxs)) return SMOE_ERR_INVALID_ARG;
   if (!ws || ((uintptr_t)ws & 255) || ws_bytes < route_workspace_bytes(T * k, E)) return SMOE_ERR_WORKSPACE;
   return launch_route((hipStream_t)stream, expert_idxs, T * k, E, sorted_expert_idxs, sorted_scattered_idxs,
@@ -322,6 +338,7 @@ int smoe_mlp_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
   int rc;
   S2SArgs fused = a1;
   fused.H = saved_H;
+  fused.grid = ctx->stream_grid;
   if (act == SMOE_ACT_SWIGLU && dtype == SMOE_BF16 && ctx->kernel_mode == 0 &&
       (s2s_decode_supported(fused) || s2s_stream_swiglu_supported(fused))) {
     // SwiGLU in the product's epilogue: H comes straight from the fp32 accumulators, and the

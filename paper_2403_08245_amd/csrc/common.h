@@ -10,7 +10,8 @@ typedef __bf16 bf16_t;
 struct smoe_ctx {
   int device;
   int num_cu;
-  int kernel_mode;  // 0 auto, 1 plain tiled kernels only
+  int stream_grid;  // blocks of the persistent kernels: one per compute unit, a multiple of 8 (one share per XCD), at most 256
+  int kernel_mode;  // 0 auto, 1 plain tiled kernels only, 2 one block per tile (testing aid, see smoe_set_kernel_mode)
 };
 
 #define SMOE_LAUNCH_CHECK()                                   \
@@ -51,6 +52,7 @@ int launch_dense_offsets(hipStream_t s, int32_t *off, int n);
 int launch_add3(hipStream_t s, const void *a, const void *b, const void *c, void *out, size_t n);
 int launch_topk_gate_bwd(hipStream_t s, const int32_t *idx, const float *gates, const float *dgates, int T, int E, int k,
                          float *dlogits);
+constexpr int ROUTE_MAX_E = 16384;   // the routing kernels keep one 4-byte counter per expert in LDS (64 KB without raising the limit)
 size_t route_workspace_bytes(int Tk, int E);
 int launch_route(hipStream_t s, const int32_t *expert_idxs, int Tk, int E, int32_t *sorted_e,
                  int32_t *sorted_s, int32_t *offsets, void *ws);
@@ -81,6 +83,7 @@ struct S2SArgs {      // C[out(i), :] = A[in(i), :] * op(W[e(i)])   for sorted r
   // Optional scratch for splitting the contraction of the last, partly filled round of tiles over the
   // compute units that would otherwise idle (S2S_TAIL_WS_BYTES of device memory, or NULL: no split).
   float *tail_ws;
+  int grid = 256;     // blocks of the persistent kernel (smoe_ctx::stream_grid)
   // Optional fused SwiGLU of Alg. 3 (forward, expert-sorted output only): W's columns are
   // [gate | up] halves of width N / 2 and H [*, N / 2] receives silu(gate) * up; C may then be
   // NULL when the pre-activation is not kept.
@@ -96,13 +99,18 @@ struct DWArgs {       // dW[e] = sum_{i in segment e} A[i, :]^T B[i, :]   (both 
   // only a fraction of the chip (a dense projection run as one expert), each segment's rows are cut into chunks
   // that leave fp32 partial tiles here, added in chunk order by a second kernel.
   float *split_ws = nullptr;
+  int grid = 256;     // blocks of the persistent kernel (smoe_ctx::stream_grid)
 };
 int launch_s2s_plain(hipStream_t s, smoe_dtype dt, const S2SArgs &a);
 int launch_dw_plain(hipStream_t s, smoe_dtype dt, const DWArgs &a);
 bool s2s_mfma_supported(const S2SArgs &a);
 bool dw_mfma_supported(const DWArgs &a);
-int launch_s2s_mfma(hipStream_t s, const S2SArgs &a, int num_cu);
-int launch_dw_mfma(hipStream_t s, const DWArgs &a, int num_cu);
+int launch_s2s_mfma(hipStream_t s, const S2SArgs &a);
+int launch_dw_mfma(hipStream_t s, const DWArgs &a);
+// Per-device set-up of the kernels that need more dynamic LDS than the default limit (called by
+// smoe_create with the context's device current).
+int init_mfma_kernels();
+int init_stream_kernels();
 // persistent tile-stream kernels (gemm_stream.hip)
 constexpr size_t S2S_TAIL_WS_BYTES = (size_t)256 * 256 * 256 * sizeof(float);   // 256 partial tiles of 256 x 256 fp32
 bool s2s_stream_supported(const S2SArgs &a);

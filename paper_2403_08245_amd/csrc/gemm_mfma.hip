@@ -323,8 +323,6 @@ template <typename K> int set_lds_limit(K kernel, int bytes) {
 }
 
 template <bool TRANS_W> int launch_s2s_cfg(hipStream_t s, const S2SArgs &a) {
-  static int attr_rc = set_lds_limit(s2s_mfma_kernel<TRANS_W>, LDS_BYTES);
-  if (attr_rc != SMOE_OK) return attr_rc;
   int tiles_n = ceil_div(a.N, TB);
   int tiles_m = ceil_div(a.Tk, TB) + a.E;     // upper bound on sum_e ceil(n_e / 256)
   int group_m = 4;
@@ -338,8 +336,6 @@ template <bool TRANS_W> int launch_s2s_cfg(hipStream_t s, const S2SArgs &a) {
 }
 
 int launch_dw_impl(hipStream_t s, const DWArgs &a) {
-  static int attr_rc = set_lds_limit(dw_mfma_kernel, LDS_BYTES);
-  if (attr_rc != SMOE_OK) return attr_rc;
   int tiles_m = ceil_div(a.M, TB), tiles_n = ceil_div(a.N, TB);
   long long total = (long long)a.E * tiles_m * tiles_n;
   if (total > 0x7fffffffLL) return SMOE_ERR_UNSUPPORTED;
@@ -355,12 +351,18 @@ int launch_dw_impl(hipStream_t s, const DWArgs &a) {
 bool s2s_mfma_supported(const S2SArgs &a) { return a.K % HK == 0 && a.N % 8 == 0 && a.ldw % 8 == 0 && a.Tk > 0; }
 bool dw_mfma_supported(const DWArgs &a) { return a.M % 8 == 0 && a.N % 8 == 0 && a.Tk > 0; }
 
-int launch_s2s_mfma(hipStream_t s, const S2SArgs &a, int num_cu) {
-  (void)num_cu;
+// Raises the dynamic LDS limit of every kernel of this file on the current device (once per context).
+int init_mfma_kernels() {
+  int rc = set_lds_limit(s2s_mfma_kernel<false>, LDS_BYTES);
+  if (rc == SMOE_OK) rc = set_lds_limit(s2s_mfma_kernel<true>, LDS_BYTES);
+  if (rc == SMOE_OK) rc = set_lds_limit(dw_mfma_kernel, LDS_BYTES);
+  return rc;
+}
+
+int launch_s2s_mfma(hipStream_t s, const S2SArgs &a) {
   return a.trans_w ? launch_s2s_cfg<true>(s, a) : launch_s2s_cfg<false>(s, a);
 }
 
-int launch_dw_mfma(hipStream_t s, const DWArgs &a, int num_cu) {
-  (void)num_cu;
+int launch_dw_mfma(hipStream_t s, const DWArgs &a) {
   return launch_dw_impl(s, a);
 }

@@ -23,7 +23,7 @@ constexpr int EPI_ROW_BYTES = 144;                        // 64 bf16 columns + 1
 constexpr int EPI_WAVE_BYTES = 32 * EPI_ROW_BYTES;
 constexpr int STREAM_LDS_BYTES = RING_BYTES + 4 * EPI_WAVE_BYTES;
 constexpr int MAX_E = 256;                                // expert offsets are cached in LDS
-constexpr int STREAM_GRID = 256;                          // persistent blocks (one per CU)
+constexpr int MAX_STREAM_GRID = 256;                      // persistent blocks: one per CU; the partial-tile scratch holds this many tiles
 
 // Epilogue of one wavefront: its 128x128 accumulators leave in 8 passes of 32 rows x 64
 // columns through a private LDS patch; every store instruction writes full 128-byte lines of
@@ -305,7 +305,10 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
   constexpr bool SWIGLU = ACT != 0;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   __shared__ int s_off[MAX_E + 1];
-  __shared__ int s_idx[3][TB];   // order indices of the rows of up to three open tiles
+  // Order indices of the rows of up to four open tiles.  With the shortest contraction the kernel takes (three
+  // half-steps) the loader has opened tile n+2 and requested the rows of tile n+3 while tile n's epilogue still
+  // reads its destination rows, so four entries are live at once.
+  __shared__ int s_idx[4][TB];
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;
@@ -348,11 +351,11 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
     t.part = split ? (w - plan.rounds * G) * plan.split + chunk : -1;
     return true;
   };
-  // order indices of a tile's 256 rows -> s_idx[ord % 3] (rows past the segment repeat its last row)
+  // order indices of a tile's 256 rows -> s_idx[ord & 3] (rows past the segment repeat its last row)
   auto fetch_rows = [&](const S2STile &t) {
     if (!o) return;
     int i = min(t.row0 + wave * 64 + lane, t.row_end - 1);
-    load4_to_lds(o + i, __builtin_amdgcn_readfirstlane(lds_address((const char *)&s_idx[t.ord % 3][0])) + uwave * 256);
+    load4_to_lds(o + i, __builtin_amdgcn_readfirstlane(lds_address((const char *)&s_idx[t.ord & 3][0])) + uwave * 256);
   };
 
   S2SStreamOps<TRANS_W> ops;
@@ -363,7 +366,7 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
     ops.base_b = (const char *)((const bf16_t *)a.W + (size_t)t.e * a.w_stride) + (size_t)t.h0 * ops.b_step;
     // gathered rows are addressed from the start of A, expert-sorted rows from the tile's first row
     ops.base_a = (const char *)(a.a_map.o ? A : A + (size_t)t.row0 * a.K) + (size_t)t.h0 * (HK * 2);
-    const int *idx = &s_idx[t.ord % 3][0];
+    const int *idx = &s_idx[t.ord & 3][0];
     const uint32_t row_bytes = (uint32_t)a.K * 2u;
 #pragma unroll
     for (int I = 0; I < NLD; ++I) {
@@ -498,7 +501,7 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
     // The next tile's first slot is opened before the epilogue: stores share the load counter,
     // so this wait would otherwise also sit out the acknowledgement of every store below.
     open_slot();
-    const int *idx = &s_idx[ct.ord % 3][wm * (TB / 2)];
+    const int *idx = &s_idx[ct.ord & 3][wm * (TB / 2)];
     const int rbase = ct.row0 + wm * (TB / 2);
     auto dst_row = [&](int r) -> int {
       int i = rbase + r;
@@ -796,8 +799,6 @@ template <bool TRANS_W, bool SCATTER_OUT, int ACT = 0> int launch_s2s_stream_cfg
                              : launch_s2s_stream_one<TRANS_W, SCATTER_OUT, ACT, false>(s, a);
 }
 template <bool TRANS_W, bool SCATTER_OUT, int ACT, bool STATIC4> int launch_s2s_stream_one(hipStream_t s, const S2SArgs &a) {
-  static int attr_rc = set_lds_limit(s2s_stream_kernel<TRANS_W, SCATTER_OUT, ACT, STATIC4>, STREAM_LDS_BYTES);
-  if (attr_rc != SMOE_OK) return attr_rc;
   int tiles_n = ACT ? ceil_div(a.N / 2, TB / 2) : ceil_div(a.N, TB);
   long long tiles_m = ceil_div(a.Tk, TB) + a.E;     // upper bound on sum_e ceil(n_e / 256)
   int group_m = 4;
@@ -805,31 +806,29 @@ template <bool TRANS_W, bool SCATTER_OUT, int ACT, bool STATIC4> int launch_s2s_
   S2SArgs args = a;
   int chunk;
   if (ACT != 0 || choose_split(a.K / HK, 4, STATIC4, chunk) == 1) args.tail_ws = nullptr;   // too short to pay: no second kernel
-  hipLaunchKernelGGL((s2s_stream_kernel<TRANS_W, SCATTER_OUT, ACT, STATIC4>), dim3(STREAM_GRID), dim3(NTHREADS), STREAM_LDS_BYTES, s, args, tiles_n,
+  hipLaunchKernelGGL((s2s_stream_kernel<TRANS_W, SCATTER_OUT, ACT, STATIC4>), dim3(a.grid), dim3(NTHREADS), STREAM_LDS_BYTES, s, args, tiles_n,
                      group_m, division_magic(a.a_map.o ? a.a_map.fan : 1));
   SMOE_LAUNCH_CHECK();
   if (args.tail_ws) {   // adds and stores the partial tiles of a split last round (no-op when nothing was split)
-    hipLaunchKernelGGL(s2s_tail_reduce_kernel<SCATTER_OUT>, dim3(STREAM_GRID - 1, TAIL_SLICES), dim3(256), 0, s, a, tiles_n, group_m,
-                       STREAM_GRID, STATIC4 ? 1 : 0);
+    hipLaunchKernelGGL(s2s_tail_reduce_kernel<SCATTER_OUT>, dim3(a.grid - 1, TAIL_SLICES), dim3(256), 0, s, a, tiles_n, group_m,
+                       a.grid, STATIC4 ? 1 : 0);
     SMOE_LAUNCH_CHECK();
   }
   return SMOE_OK;
 }
 
 int launch_dw_stream_impl(hipStream_t s, const DWArgs &a) {
-  static int attr_rc = set_lds_limit(dw_stream_kernel, STREAM_LDS_BYTES);
-  if (attr_rc != SMOE_OK) return attr_rc;
   int tiles_m = ceil_div(a.M, TB), tiles_n = ceil_div(a.N, TB);
   // Row split: only when every tile of every expert, times the split, fits one round of the grid, and only when
   // it shortens the contraction by more than the partial tiles cost (as for the split last round above).
   int split = 1;
   const long long tiles = (long long)a.E * tiles_m * tiles_n;
-  if (a.split_ws && tiles * 2 <= STREAM_GRID) {
+  if (a.split_ws && tiles * 2 <= a.grid) {
     const long long nh = a.Tk / a.E / HK;            // half-steps of an average segment
-    split = (int)(STREAM_GRID / tiles < 8 ? STREAM_GRID / tiles : 8);
+    split = (int)(a.grid / tiles < 8 ? a.grid / tiles : 8);
     if (nh - nh / split < SPLIT_MIN_SAVED) split = 1;
   }
-  hipLaunchKernelGGL(dw_stream_kernel, dim3(STREAM_GRID), dim3(NTHREADS), STREAM_LDS_BYTES, s, a, tiles_m, tiles_n, split);
+  hipLaunchKernelGGL(dw_stream_kernel, dim3(a.grid), dim3(NTHREADS), STREAM_LDS_BYTES, s, a, tiles_m, tiles_n, split);
   SMOE_LAUNCH_CHECK();
   if (split > 1) {
     hipLaunchKernelGGL(dw_split_reduce_kernel, dim3((unsigned)tiles, TAIL_SLICES), dim3(256), 0, s, a, tiles_m, tiles_n, split);
@@ -848,7 +847,7 @@ bool s2s_stream_supported(const S2SArgs &a) {
   // sorted A, from the start of an expert's matrix) must fit the 32-bit offset of the loads
   long long a_rows = a.a_map.o ? (long long)a.Tk / fan + 1 : TB;
   long long w_rows = a.trans_w ? a.N : a.K;
-  return a.K % HK == 0 && a.K >= 3 * HK && a.N % 8 == 0 && a.ldw % 8 == 0 && a.Tk > 0 && a.E <= MAX_E &&
+  return a.grid >= 8 && a.grid % 8 == 0 && a.grid <= MAX_STREAM_GRID && a.K % HK == 0 && a.K >= 3 * HK && a.N % 8 == 0 && a.ldw % 8 == 0 && a.Tk > 0 && a.E <= MAX_E &&
          (long long)a.Tk * fan < 0x100000000LL && a_rows * a.K * 2 < 0x100000000LL &&
          (w_rows + HK) * a.ldw * 2 < 0x100000000LL;
 }
@@ -869,7 +868,23 @@ int launch_s2s_stream(hipStream_t s, const S2SArgs &a) {
 
 bool dw_stream_supported(const DWArgs &a) {
   long long tiles = (long long)a.E * ceil_div(a.M, TB) * ceil_div(a.N, TB);
-  return a.M % 8 == 0 && a.N % 8 == 0 && a.Tk > 0 && a.E <= MAX_E && tiles + STREAM_GRID < 0x7fffffffLL;
+  return a.M % 8 == 0 && a.N % 8 == 0 && a.Tk > 0 && a.E <= MAX_E && tiles + MAX_STREAM_GRID < 0x7fffffffLL && a.grid >= 8 && a.grid % 8 == 0 && a.grid <= MAX_STREAM_GRID;
 }
 
 int launch_dw_stream(hipStream_t s, const DWArgs &a) { return launch_dw_stream_impl(s, a); }
+
+// Raises the dynamic LDS limit of every persistent kernel on the current device (once per context).
+template <bool TRANS_W, bool SCATTER_OUT, int ACT> static int init_s2s_pair() {
+  int rc = set_lds_limit(s2s_stream_kernel<TRANS_W, SCATTER_OUT, ACT, false>, STREAM_LDS_BYTES);
+  return rc != SMOE_OK ? rc : set_lds_limit(s2s_stream_kernel<TRANS_W, SCATTER_OUT, ACT, true>, STREAM_LDS_BYTES);
+}
+int init_stream_kernels() {
+  int rc = init_s2s_pair<false, false, 0>();
+  if (rc == SMOE_OK) rc = init_s2s_pair<false, true, 0>();
+  if (rc == SMOE_OK) rc = init_s2s_pair<true, false, 0>();
+  if (rc == SMOE_OK) rc = init_s2s_pair<true, true, 0>();
+  if (rc == SMOE_OK) rc = init_s2s_pair<false, false, 1>();
+  if (rc == SMOE_OK) rc = init_s2s_pair<false, false, 2>();
+  if (rc == SMOE_OK) rc = set_lds_limit(dw_stream_kernel, STREAM_LDS_BYTES);
+  return rc;
+}

@@ -5,7 +5,9 @@
 // ---------------------------------------------------------------------------------------
 // top-k gate: one thread per token.  Slot j takes the largest logit that comes after slot
 // j-1's pick in the order (value descending, expert id ascending), so ties go to the lower
-// id and no per-thread array is needed.  Gates are the softmax over the k picks.
+// id and no per-thread array is needed.  Gates are the softmax over the k picks.  A NaN logit
+// counts as -inf (it can only be kept after every number), and picks that are all -inf share
+// the weight equally, so every token writes all k slots whatever its logits hold.
 // ---------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) topk_gate_kernel(const float *__restrict__ logits, int T, int E, int k,
                                                         int32_t *__restrict__ idx, float *__restrict__ gates) {
@@ -19,12 +21,13 @@ __global__ void __launch_bounds__(256) topk_gate_kernel(const float *__restrict_
     int best_i = -1;
     for (int e = 0; e < E; ++e) {
       float v = row[e];
+      if (v != v) v = -INFINITY;
       bool after_prev = (prev_i < 0) || (v < prev_v) || (v == prev_v && e > prev_i);
       bool better = (best_i < 0) || (v > best_v);  // first hit wins ties -> lower id
       if (after_prev && better) { best_v = v; best_i = e; }
     }
     if (j == 0) first_v = best_v;
-    float w = expf(best_v - first_v);
+    float w = first_v == -INFINITY ? 1.0f : expf(best_v - first_v);
     idx[(size_t)t * k + j] = best_i;
     gates[(size_t)t * k + j] = w;
     sum += w;
@@ -53,6 +56,7 @@ __global__ void __launch_bounds__(256) topk_gate_wave_kernel(const float *__rest
     int e = lane + 64 * i;
     // padding ranks after every real logit and never before one (-inf loses ties to the lower real ids)
     v[i] = e < E ? logits[(size_t)t * E + e] : -INFINITY;
+    if (v[i] != v[i]) v[i] = -INFINITY;   // NaN counts as -inf
     row[e] = v[i];
     rank[i] = 0;
   }
@@ -74,7 +78,7 @@ __global__ void __launch_bounds__(256) topk_gate_wave_kernel(const float *__rest
   float w[VPL], sum = 0.f;
 #pragma unroll
   for (int i = 0; i < VPL; ++i) {
-    w[i] = (rank[i] < k && lane + 64 * i < E) ? expf(v[i] - top) : 0.f;
+    w[i] = (rank[i] < k && lane + 64 * i < E) ? (top == -INFINITY ? 1.0f : expf(v[i] - top)) : 0.f;
     sum += w[i];
   }
 #pragma unroll

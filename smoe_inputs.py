@@ -165,11 +165,16 @@ def custom(name="custom", **kw) -> MLPConfig:
     return replace(base, **kw)
 
 
-def plinear_case(T, d_in, d_out, E, k, dtype="f32", seed=0, x_rows=None) -> dict:
-    """Tensors for one ParallelLinear call: logits, X [x_rows,d_in], W [E,d_in,d_out], dY rows."""
+def plinear_case(T, d_in, d_out, E, k, dtype="f32", seed=0, x_rows=None, zipf_s=0.0) -> dict:
+    """Tensors for one ParallelLinear call: logits, X [x_rows,d_in], W [E,d_in,d_out], dY rows.
+    zipf_s > 0 adds the fitted per-expert bias that makes the expert loads follow Zipf(s)."""
     x_rows = T if x_rows is None else x_rows
+    logits = torch.randn(T, E, generator=_gen(seed, 11), dtype=torch.float32)
+    if zipf_s > 0:
+        b = fit_router_bias(logits.numpy().astype(np.float64), k, zipf_shares(E, zipf_s), iters=100)
+        logits = logits + torch.from_numpy(b.astype(np.float32))
     return dict(
-        logits=torch.randn(T, E, generator=_gen(seed, 11), dtype=torch.float32),
+        logits=logits,
         X=normal((x_rows, d_in), 1.0, seed, 12, dtype),
         W=normal((E, d_in, d_out), 1.0 / math.sqrt(d_in), seed, 13, dtype),
         dY_T=normal((T, d_out), 1.0, seed, 14, dtype),

@@ -1,3 +1,4 @@
+import math
 import os
 import sys
 
@@ -15,3 +16,58 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+class GuardedAllocator:
+    """Stands in for the binding's one allocation function during the GPU tests.
+
+    Every output, saved tensor and workspace the binding creates is filled with 0xFF bytes (a NaN in
+    bf16 and fp32, -1 in int32), so a row or tile the kernels fail to write shows up as a non-finite or
+    negative entry instead of whatever an earlier, correct call left in a recycled block; and it sits
+    between two guard bands holding a byte pattern that must be intact when the test ends, so a store
+    that lands just outside a tensor is caught even though the memory belongs to the process."""
+
+    GUARD = 256 * 1024          # bytes on each side; a multiple of 256 keeps the payload's alignment
+    PATTERN, POISON = 0xA5, 0xFF
+
+    def __init__(self):
+        self.live = []
+
+    def __call__(self, *shape, dtype, device):
+        import torch
+        if len(shape) == 1 and isinstance(shape[0], (tuple, list, torch.Size)):
+            shape = tuple(shape[0])
+        es = torch.empty(0, dtype=dtype).element_size()
+        nbytes = math.prod(shape) * es
+        body = (nbytes + 255) // 256 * 256
+        raw = torch.empty(2 * self.GUARD + body, dtype=torch.uint8, device=device)
+        raw.fill_(self.PATTERN)
+        raw[self.GUARD:self.GUARD + nbytes].fill_(self.POISON)
+        self.live.append((raw, nbytes, tuple(shape), dtype))
+        return raw[self.GUARD:self.GUARD + nbytes].view(dtype).view(*shape)
+
+    def check(self):
+        import torch
+        torch.cuda.synchronize()
+        for raw, nbytes, shape, dtype in self.live:
+            lo, hi = raw[:self.GUARD], raw[self.GUARD + nbytes:]
+            assert bool((lo == self.PATTERN).all()), f"bytes written in front of a {dtype} tensor of shape {shape}"
+            assert bool((hi == self.PATTERN).all()), f"bytes written behind a {dtype} tensor of shape {shape}"
+        self.live.clear()
+
+
+@pytest.fixture(autouse=True)
+def guarded_outputs(request):
+    """GPU tests run with poisoned, guard-banded outputs and workspaces (see GuardedAllocator)."""
+    if request.node.get_closest_marker("gpu") is None:
+        yield None
+        return
+    import paper_2403_08245_amd as m
+    alloc = GuardedAllocator()
+    saved = m._new
+    m._new = alloc
+    try:
+        yield alloc
+    finally:
+        m._new = saved
+    alloc.check()

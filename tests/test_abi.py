@@ -71,3 +71,28 @@ def test_workspace_queries_are_pure_host_arithmetic():
     many = lib.smoe_attention_bwd_workspace_bytes(16, 2048, 4, 8)    # 128 pairs: whole lists
     assert many == 16 * 2048 * 4 * 8 * 4
     assert few > 2 * 4096 * 4 * 4 * 4
+
+
+def test_guarded_allocator_poisons_and_catches_stray_writes(monkeypatch):
+    """The allocator the GPU tests install (conftest.py), tried on CPU tensors: new tensors read as NaN / -1,
+    writes inside a tensor pass the check, a write just outside trips it."""
+    import pytest
+    import torch
+    from conftest import GuardedAllocator
+    monkeypatch.setattr(torch.cuda, "synchronize", lambda: None)
+    a = GuardedAllocator()
+    x = a(5, 7, dtype=torch.bfloat16, device="cpu")
+    i = a(9, dtype=torch.int32, device="cpu")
+    assert x.shape == (5, 7) and torch.isnan(x.float()).all() and (i == -1).all()
+    x.zero_(); i.zero_()
+    a.check()
+    b = GuardedAllocator()
+    b(4, dtype=torch.float32, device="cpu")
+    b.live[0][0][GuardedAllocator.GUARD + 16] = 0        # first byte behind the 16-byte payload
+    with pytest.raises(AssertionError, match="behind"):
+        b.check()
+    c = GuardedAllocator()
+    c(4, dtype=torch.float32, device="cpu")
+    c.live[0][0][GuardedAllocator.GUARD - 1] = 0         # last byte in front of it
+    with pytest.raises(AssertionError, match="in front"):
+        c.check()

@@ -14,7 +14,7 @@ import torch
 
 import oracle
 import smoe_inputs as si
-from helpers import TOL, oracle_routing, rel_err
+from helpers import ROW_MIN_WIDTH, TOL, oracle_gates_f32, oracle_routing, rel_err, row_rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -57,12 +57,15 @@ def _sample_tokens(ei, E, per_expert, seed):
     return sorted(chosen, key=lambda t: tuple(sorted(ei[t].tolist())))
 
 
-def _check(name, gpu, ref, tol, scale=None):
+def _check(name, gpu, ref, tol, scale=None, rows=True):
     g = gpu.detach().to(torch.float32).cpu().numpy().astype(np.float64) if isinstance(gpu, torch.Tensor) else gpu
     assert np.isfinite(g).all(), name
     denom = scale if scale is not None else np.abs(ref).max()
     err = float(np.abs(g - ref).max() / (denom if denom > 0 else 1.0))
     assert err <= tol, f"{name}: {err:.3e} > {tol}"
+    if rows and scale is None and np.ndim(ref) >= 2 and np.shape(ref)[-1] >= ROW_MIN_WIDTH:
+        er = row_rel_err(g, ref)            # every sampled row against its own scale
+        assert er <= tol, f"{name}: per-row {er:.3e} > {tol}"
     return err
 
 
@@ -92,7 +95,7 @@ def _run_fullsize(smoe, cfg, seed, tokens_per_expert, dw_samples, backward=True,
     torch.cuda.synchronize()
     _log(f"{cfg.name}: GPU pass done at {time.time() - t0:.1f}s")
 
-    g64 = gg.cpu().numpy().astype(np.float64)
+    g64 = oracle_gates_f32(g)
     X32 = si.as_f32(case["X"])
     W1c, W2c = ExpertCache(si.as_f32(case["W1"])), ExpertCache(si.as_f32(case["W2"]))
     dY32 = si.as_f32(case["dY"]) if backward else None
@@ -146,8 +149,10 @@ def _run_fullsize(smoe, cfg, seed, tokens_per_expert, dw_samples, backward=True,
             r2.append(ref2); g2.append(got2); r1.append(ref1); g1.append(got1.astype(np.float64))
             if e % 8 == 0:
                 _log(f"{cfg.name}: dW samples expert {e} at {time.time() - t0:.1f}s")
-        errs["dW2"] = _check(f"{cfg.name} dW2 rows", np.stack(g2), np.stack(r2), tol)
-        errs["dW1"] = _check(f"{cfg.name} dW1 cols", np.stack(g1), np.stack(r1), tol)
+        # (no per-row scale here: a sampled row of dW2 / column of dW1 is a hidden-unit scalar per token times a
+        # token row, and with one or two tokens in an expert that scalar can be a near-cancelled sum)
+        errs["dW2"] = _check(f"{cfg.name} dW2 rows", np.stack(g2), np.stack(r2), tol, rows=False)
+        errs["dW1"] = _check(f"{cfg.name} dW1 cols", np.stack(g1), np.stack(r1), tol, rows=False)
     _log(cfg.name, "max rel err:", {k: f"{v:.2e}" for k, v in errs.items()}, f"({time.time() - t0:.1f}s)")
 
 
@@ -236,7 +241,8 @@ def test_C5_moa_projections_scatter_to_scatter(smoe):
     # all tokens but a single input feature (row c of dW[e] depends on column c of the input only).
     X64, WQ64, Oh64, WO64 = (si.as_f64(t) for t in (cq["X"], cq["W"], co["X"], co["W"]))
     dQ64, dO64 = si.as_f64(cq["dY_Tk"]), si.as_f64(co["dY_T"])
-    g64 = gg.cpu().numpy().astype(np.float64)
+    assert np.abs(gg.cpu().numpy() - g).max() <= 1e-6
+    g64 = oracle_gates_f32(g)
     rng = np.random.default_rng(7)
     S = np.sort(rng.choice(T, size=48, replace=False))
     slots = (S[:, None] * k + np.arange(k)[None, :]).reshape(-1)

@@ -10,7 +10,7 @@ import torch
 
 import oracle
 import smoe_inputs as si
-from helpers import TOL, assert_close, dev, oracle_routing, rel_err, torch_dtype
+from helpers import TOL, assert_close, dev, oracle_gates_f32, oracle_routing, rel_err, torch_dtype
 
 pytestmark = pytest.mark.gpu
 
@@ -76,6 +76,26 @@ def test_topk_ties_and_quantised_logits(smoe, E, k):
     assert np.abs(gg.cpu().numpy() - gates).max() <= 1e-6
 
 
+@pytest.mark.parametrize("E,k", [(4, 3), (70, 8), (130, 5), (256, 256), (300, 7)])
+def test_topk_with_nan_and_infinite_logits(smoe, E, k):
+    """NaN counts as -inf, kept logits that are all -inf share the weight equally: every slot of every token is
+    written (outputs are poisoned beforehand) and equals the oracle's, in the wavefront-per-token and the
+    thread-per-token kernels alike."""
+    gen = torch.Generator().manual_seed(E)
+    logits = torch.randn(600, E, generator=gen, dtype=torch.float32)
+    u = torch.rand(600, E, generator=gen)
+    logits[u < 0.2] = float("nan")
+    logits[(u >= 0.2) & (u < 0.35)] = -float("inf")
+    logits[0] = float("nan")                       # nothing to choose from
+    logits[1] = -float("inf")
+    logits[2, 1:] = float("nan")                   # exactly one number
+    ei, gates, se, o, off = oracle_routing(logits, k, E)
+    gi, gg = smoe.topk_gate(logits.cuda(), k)
+    assert np.array_equal(gi.cpu().numpy(), ei)
+    got = gg.cpu().numpy()
+    assert np.isfinite(got).all() and np.abs(got - gates).max() <= 1e-6
+
+
 @pytest.mark.parametrize("pattern", ["one_expert", "empty_middle", "k_equals_E", "masked"])
 def test_route_degenerate_distributions(smoe, pattern):
     T, E, k = 300, 8, 2
@@ -135,7 +155,8 @@ def test_plinear_forward_and_backward(smoe, shape, gin, gout, with_p, dtype):
     c, (ei, g, se, o, off), (gi, gg, r) = _plinear_setup(smoe, T, d_in, d_out, E, k, dtype, 7, gin)
     fan = 1 if gin else k
     X, W = si.as_f64(c["X"]), si.as_f64(c["W"])
-    p64 = gg.cpu().numpy().astype(np.float64) if with_p else None       # the f32 gates the GPU uses
+    assert np.abs(gg.cpu().numpy().astype(np.float64) - g).max() <= 1e-6
+    p64 = oracle_gates_f32(g) if with_p else None       # the oracle's own gates, in the precision they are stored in
     Y_ref, Yhat_ref = oracle.plinear_fwd(X, W, se, o, fan, p64, bool(gin), bool(gout))
     Y, Yhat = smoe.plinear_fwd(c["X"].cuda(), c["W"].cuda(), r, fan, gg if with_p else None, bool(gin), bool(gout))
     assert_close(Yhat, Yhat_ref, td, "Yhat")
@@ -159,7 +180,7 @@ def test_plinear_weight_gradient_with_few_tiles_and_many_rows(smoe, E, gin, gout
     td = torch.bfloat16
     c, (ei, g, se, o, off), (gi, gg, r) = _plinear_setup(smoe, T, d_in, d_out, E, k, "bf16", 21, gin)
     X, W = si.as_f64(c["X"]), si.as_f64(c["W"])
-    p64 = gg.cpu().numpy().astype(np.float64) if with_p else None
+    p64 = oracle_gates_f32(g) if with_p else None
     Y, Yhat = smoe.plinear_fwd(c["X"].cuda(), c["W"].cuda(), r, k, gg if with_p else None, bool(gin), bool(gout))
     dY_t = c["dY_T"] if with_p else c["dY_Tk"]
     dX_ref, dW_ref, dp_ref = oracle.plinear_bwd(si.as_f64(dY_t), X, W, se, o, k, p64, bool(gin), bool(gout))
@@ -198,7 +219,8 @@ def _mlp_parity(smoe, cfg, seed, plain=False, mode=None):
         torch.cuda.synchronize()
     finally:
         smoe.set_kernel_mode(0)
-    g64 = gg.cpu().numpy().astype(np.float64)
+    assert np.abs(gg.cpu().numpy().astype(np.float64) - g).max() <= 1e-6
+    g64 = oracle_gates_f32(g)
     X64, W164, W264, dY64 = (si.as_f64(case[n]) for n in ("X", "W1", "W2", "dY"))
     ref = oracle.mlp_fwd(X64, W164, W264, ei, g64, cfg.act)
     errs = {}
@@ -311,7 +333,7 @@ def test_mlp_inference_mode_matches_training_forward(smoe, name):
     assert torch.equal(Yt, Yi)
     ei, g = oracle.topk_gate(case["logits"].numpy(), cfg.k)
     ref = oracle.mlp_fwd(si.as_f64(case["X"]), si.as_f64(case["W1"]), si.as_f64(case["W2"]), ei,
-                         gg.cpu().numpy().astype(np.float64), cfg.act)
+                         oracle_gates_f32(g), cfg.act)
     assert_close(Yi, ref["Y"], torch_dtype(cfg.dtype), f"{name} inference Y")
 
 
