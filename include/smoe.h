@@ -54,7 +54,8 @@ typedef enum {
   SMOE_ERR_INVALID_ARG = -1,   /* null pointer, non-positive size, inconsistent flags   */
   SMOE_ERR_UNSUPPORTED = -2,   /* valid request this build has no kernel for            */
   SMOE_ERR_WORKSPACE = -3,     /* ws is NULL / misaligned / smaller than required       */
-  SMOE_ERR_HIP = -4            /* a HIP runtime call (launch, device query) failed      */
+  SMOE_ERR_HIP = -4,           /* a HIP runtime call (launch, device query) failed      */
+  SMOE_ERR_TOO_LARGE = -5      /* beyond the fixed scratch of a no-allocation entry point */
 } smoe_status;
 
 /* The routing products of Sec. 3.1 step 2 ("sort the tokens according to the experts").
@@ -113,6 +114,20 @@ size_t smoe_route_workspace_bytes(int T, int k, int E);
 int smoe_route(smoe_ctx *ctx, void *stream, const int32_t *expert_idxs, int T, int k, int E,
                int32_t *sorted_expert_idxs, int32_t *sorted_scattered_idxs,
                int32_t *expert_offsets, void *ws, size_t ws_bytes);
+
+/* smoe_route for callers that cannot allocate or pass a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid device allocation.  Same inputs, outputs and results as smoe_route;
+ * the per-chunk expert counts live in a fixed 1 MiB device array inside the library (one copy per GPU the
+ * library runs on, held until the process ends) whose address smoe_create looks up for the context's
+ * device.  Limit: ceil(T*k / 1024) * E * 4 bytes (rounded up to 256) must not exceed 1 MiB, e.g. up to
+ * 1 Mi routed slots with 256 experts, else SMOE_ERR_TOO_LARGE and nothing is enqueued.  Calls no
+ * allocator, no memset and no synchronisation.  Every call on one GPU uses the same array: calls that
+ * overlap on one GPU (different streams, or threads) race and must be serialised by the caller; calls
+ * in stream order on one stream are fine.  The array keeps the last call's contents; nothing in it needs
+ * clearing, each call overwrites every counter it reads. */
+int smoe_route_noalloc(smoe_ctx *ctx, void *stream, const int32_t *expert_idxs, int T, int k, int E,
+                       int32_t *sorted_expert_idxs, int32_t *sorted_scattered_idxs,
+                       int32_t *expert_offsets);
 
 /* ---- ParallelLinear forward: Alg. 1 (scatter2scatter, Sec. 3.2, Fig. 2) --------------
  *   X     [x_rows, d_in]  grouped_in = 0: scattered, the row of slot s is s / k (fan-out k,

@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(_PKG, "libsmoe.so")
 
 EXPORTS = [
     "smoe_create", "smoe_destroy", "smoe_strerror", "smoe_abi_version", "smoe_set_kernel_mode",
-    "smoe_topk_gate", "smoe_topk_gate_bwd", "smoe_route_workspace_bytes", "smoe_route",
+    "smoe_topk_gate", "smoe_topk_gate_bwd", "smoe_route_workspace_bytes", "smoe_route", "smoe_route_noalloc",
     "smoe_plinear_fwd", "smoe_plinear_bwd_workspace_bytes", "smoe_plinear_bwd",
     "smoe_mlp_fwd_workspace_bytes", "smoe_mlp_fwd", "smoe_mlp_bwd_workspace_bytes", "smoe_mlp_bwd",
     "smoe_group", "smoe_attention_fwd", "smoe_attention_bwd_workspace_bytes", "smoe_attention_bwd",
@@ -71,6 +71,7 @@ lib.smoe_momha_bwd.argtypes = [_vp, _vp, _i, _vp, _vp, _i, _i, _i, _i, _i, _vp, 
 lib.smoe_route_workspace_bytes.argtypes = [_i, _i, _i]
 lib.smoe_route_workspace_bytes.restype = _sz
 lib.smoe_route.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _sz]
+lib.smoe_route_noalloc.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp]
 lib.smoe_plinear_fwd.argtypes = [_vp, _vp, _i, _vp, _i, _i, _vp, _i, _rp, _i, _vp, _i, _i, _i, _vp, _vp]
 lib.smoe_plinear_bwd_workspace_bytes.argtypes = [_i] * 9
 lib.smoe_plinear_bwd_workspace_bytes.restype = _sz
@@ -274,6 +275,17 @@ def route(expert_idxs: torch.Tensor, E: int) -> Routing:
     _check(lib.smoe_route(ctx(), _stream(), _p(expert_idxs), T, k, E, _p(se), _p(so), _p(off), _p(ws), ws.numel()),
            "smoe_route")
     return Routing(se, so, off, T * k, E)
+
+
+def route_noalloc(expert_idxs: torch.Tensor, E: int, out: Routing) -> Routing:
+    """smoe_route_noalloc: routing into the caller's arrays `out`, scratch inside the library."""
+    _chk(expert_idxs, torch.int32)
+    T, k = expert_idxs.shape
+    if out.sorted_expert_idxs.numel() < T * k or out.expert_offsets.numel() < E + 1:
+        raise ValueError("output arrays too small")
+    _check(lib.smoe_route_noalloc(ctx(), _stream(), _p(expert_idxs), T, k, E, _p(out.sorted_expert_idxs),
+                                  _p(out.sorted_scattered_idxs), _p(out.expert_offsets)), "smoe_route_noalloc")
+    return Routing(out.sorted_expert_idxs, out.sorted_scattered_idxs, out.expert_offsets, T * k, E)
 
 
 def group(x: torch.Tensor, r: Routing, fan: int, gates: torch.Tensor | None = None) -> torch.Tensor:

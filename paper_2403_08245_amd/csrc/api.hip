@@ -59,6 +59,7 @@ const char *smoe_strerror(int status) {
     case SMOE_ERR_UNSUPPORTED: return "unsupported shape or option (row widths must be multiples of 16 bytes)";
     case SMOE_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case SMOE_ERR_HIP: return "HIP runtime error";
+    case SMOE_ERR_TOO_LARGE: return "problem exceeds the fixed scratch capacity of a no-allocation entry point";
     default: return "unknown status";
   }
 }
@@ -78,12 +79,14 @@ int smoe_create(smoe_ctx **out, int device) {
   // persistent kernels: one block per compute unit, dealt to the XCDs in eight equal shares
   c->stream_grid = c->num_cu >= 256 ? 256 : (c->num_cu & ~7);
   c->kernel_mode = 0;
-  // kernel attributes are per device: set them with this context's device current, then restore the caller's
+  c->route_scratch = nullptr;
+  // kernel attributes and the address of a __device__ array are per device: set them with this context's device current, then restore the caller's
   int prev = -1;
   int rc = SMOE_ERR_HIP;
   if (hipGetDevice(&prev) == hipSuccess && hipSetDevice(device) == hipSuccess) {
     rc = init_stream_kernels();
     if (rc == SMOE_OK) rc = init_mfma_kernels();
+    if (rc == SMOE_OK) rc = route_scratch_address(&c->route_scratch);
     if (hipSetDevice(prev) != hipSuccess && rc == SMOE_OK) rc = SMOE_ERR_HIP;
   }
   if (rc != SMOE_OK) {
@@ -166,6 +169,19 @@ int smoe_route(smoe_ctx *ctx, void *stream, const int32_t *expert_idxs, int T, i
   if (!ws || ((uintptr_t)ws & 255) || ws_bytes < route_workspace_bytes(T * k, E)) return SMOE_ERR_WORKSPACE;
   return launch_route((hipStream_t)stream, expert_idxs, T * k, E, sorted_expert_idxs, sorted_scattered_idxs,
                       expert_offsets, ws);
+}
+
+int smoe_route_noalloc(smoe_ctx *ctx, void *stream, const int32_t *expert_idxs, int T, int k, int E,
+                       int32_t *sorted_expert_idxs, int32_t *sorted_scattered_idxs, int32_t *expert_offsets) {
+  if (!ctx || T < 0 || k < 1 || E < 1 || !expert_offsets) return SMOE_ERR_INVALID_ARG;
+  if ((long long)T * k > 0x7fffffffLL || E > ROUTE_MAX_E) return SMOE_ERR_UNSUPPORTED;
+  if (T > 0 && (!expert_idxs || !sorted_expert_idxs || !sorted_scattered_idxs)) return SMOE_ERR_INVALID_ARG;
+  if (route_workspace_bytes(T * k, E) > ROUTE_SCRATCH_BYTES) return SMOE_ERR_TOO_LARGE;
+  if (!ctx->route_scratch) return SMOE_ERR_HIP;
+  // Nothing in the scratch has to start at zero: the counting kernel writes every (expert, chunk) counter
+  // before the scan reads it, and a one-chunk problem does not touch the scratch at all.
+  return launch_route((hipStream_t)stream, expert_idxs, T * k, E, sorted_expert_idxs, sorted_scattered_idxs,
+                      expert_offsets, ctx->route_scratch);
 }
 
 int smoe_group(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *in, int d, const smoe_routing *r, int fan,

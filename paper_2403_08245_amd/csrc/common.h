@@ -12,6 +12,7 @@ struct smoe_ctx {
   int num_cu;
   int stream_grid;  // blocks of the persistent kernels: one per compute unit, a multiple of 8 (one share per XCD), at most 256
   int kernel_mode;  // 0 auto, 1 plain tiled kernels only, 2 one block per tile (testing aid, see smoe_set_kernel_mode)
+  int32_t *route_scratch;  // this device's copy of the routing kernels' static scratch array (smoe_route_noalloc)
 };
 
 #define SMOE_LAUNCH_CHECK()                                   \
@@ -54,6 +55,9 @@ int launch_topk_gate_bwd(hipStream_t s, const int32_t *idx, const float *gates, 
                          float *dlogits);
 constexpr int ROUTE_MAX_E = 16384;   // the routing kernels keep one 4-byte counter per expert in LDS (64 KB without raising the limit)
 size_t route_workspace_bytes(int Tk, int E);
+// Static device scratch of smoe_route_noalloc: its size, and the address of the current device's copy.
+constexpr size_t ROUTE_SCRATCH_BYTES = (size_t)1 << 20;
+int route_scratch_address(int32_t **ptr);
 int launch_route(hipStream_t s, const int32_t *expert_idxs, int Tk, int E, int32_t *sorted_e,
                  int32_t *sorted_s, int32_t *offsets, void *ws);
 

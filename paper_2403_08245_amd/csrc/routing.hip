@@ -295,6 +295,20 @@ __global__ void __launch_bounds__(64) route_single_chunk_kernel(const int32_t *_
   }
 }
 
+// Scratch of the no-allocation routing entry point: the per-chunk expert counts that smoe_route keeps in
+// caller workspace live here instead.  One copy per device, held until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress: kernels get the address looked up below.
+static __device__ __align__(256) int32_t scratch[ROUTE_SCRATCH_BYTES / sizeof(int32_t)];
+
+// Address of the current device's copy of the scratch array (called once per context, with the context's
+// device current).
+int route_scratch_address(int32_t **ptr) {
+  void *p = nullptr;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return SMOE_ERR_HIP;
+  *ptr = (int32_t *)p;
+  return SMOE_OK;
+}
+
 size_t route_workspace_bytes(int Tk, int E) {
   size_t nchunk = (size_t)ceil_div(Tk > 0 ? Tk : 1, ROUTE_CHUNK);
   return align256(nchunk * (size_t)E * sizeof(int32_t));
