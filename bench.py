@@ -4,9 +4,11 @@
 One "step" = top-k gate, routing sort, SMoE MLP forward and backward over one synthetic
 batch that is already resident in HBM.  Prints ONE JSON line:
   metric/value  GEMM TFLOP/s of fwd+bwd (6 grouped GEMMs, 2*Tk*d_model*(d_h+d_expert)*3 flop)
-  roofline      the dominant kernel (scatter2scatter of the first ParallelLinear) timed alone
-                with HIP events against the dense bf16 MFMA peak
-  cpu_baseline  the fp64 CPU oracle timed on a few sampled tokens of the same workload
+  roofline      the dominant kernel of the step (the first ParallelLinear's scatter2scatter, with the SwiGLU
+                epilogue it has inside the step) timed with HIP events on the launch stream, against the
+                roofline that bounds it (dense bf16 MFMA peak or HBM bandwidth), the other one alongside
+  forward_hbm   the whole forward pass against its algorithmic HBM bytes
+  cpu_baseline  the fp64 CPU oracle timed on sampled tokens of the same workload, one thread and all threads
 """
 from __future__ import annotations
 
@@ -31,34 +33,67 @@ def _events(n):
     return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
 
 
-def cpu_baseline(case, cfg, gates_np, ei_np, budget_s: float):
-    """Times the oracle's per-token forward+backward on sampled tokens (bounded CPU work)."""
+class _F64Experts:
+    """float64 copies of the expert matrices, made once per expert before the clock starts (the oracle converts
+    whatever it is handed to float64; handing it float64 keeps that conversion out of the timed region)."""
+
+    def __init__(self, w32: np.ndarray, experts):
+        self.shape = w32.shape
+        self.m = {int(e): w32[int(e)].astype(np.float64) for e in experts}
+
+    def __getitem__(self, e):
+        return self.m[int(e)]
+
+
+def cpu_baseline(case, cfg, budget_s: float):
+    """Times the oracle as it stands (per-token fp64 forward + analytic backward, Sec. 3.1's naive loop) on a
+    bounded random sample of the workload's tokens: half the budget with the BLAS pool limited to one thread,
+    half with the pool as the box gives it.  Routing comes from the oracle's own top-k, not from the GPU."""
     import oracle
     import smoe_inputs as si
-    try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        threads = 1
-    X = si.as_f32(case["X"]); dY = si.as_f32(case["dY"])
-    W1 = si.as_f32(case["W1"]); W2 = si.as_f32(case["W2"])
+    from threadpoolctl import threadpool_info, threadpool_limits
+    pool = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     rng = np.random.default_rng(0)
-    order = rng.permutation(cfg.T)
-    t0 = time.perf_counter()
-    n = 0
-    for t in order:
-        oracle.mlp_token_fwd(X[t], ei_np[t], gates_np[t], W1, W2, cfg.act)
-        oracle.mlp_token_bwd(X[t], dY[t], ei_np[t], gates_np[t], W1, W2, cfg.act)
-        n += 1
-        if time.perf_counter() - t0 > budget_s or n >= 4096:
-            break
-    dt = time.perf_counter() - t0
+    cand = rng.permutation(cfg.T)[:256]
+    logits = case["logits"].numpy()
+    ei, g = oracle.topk_gate(logits[cand], cfg.k)
+    g = g.astype(np.float32).astype(np.float64)
+    # tokens whose experts are among the few whose matrices are converted up front (bounds host memory and set-up time)
+    per_expert_bytes = 8.0 * cfg.d_model * (cfg.d_h + cfg.d_expert)
+    n_keep = int(max(cfg.k, min(cfg.E, 8e9 // per_expert_bytes)))
+    counts = np.bincount(ei.reshape(-1), minlength=cfg.E)
+    keep = set(np.argsort(-counts, kind="stable")[:n_keep].tolist())
+    rows = [i for i in range(len(cand)) if set(ei[i].tolist()) <= keep]
+    X = si.as_f32(case["X"]); dY = si.as_f32(case["dY"])
+    W1 = _F64Experts(si.as_f32(case["W1"]), keep)
+    W2 = _F64Experts(si.as_f32(case["W2"]), keep)
     flops_per_token = 3.0 * cfg.gemm_flops_fwd() / cfg.T
+
+    def leg(seconds, start):
+        t0, c0 = time.perf_counter(), time.process_time()
+        n = 0
+        while True:
+            i = rows[(start + n) % len(rows)]
+            t = cand[i]
+            oracle.mlp_token_fwd(X[t], ei[i], g[i], W1, W2, cfg.act)
+            oracle.mlp_token_bwd(X[t], dY[t], ei[i], g[i], W1, W2, cfg.act)
+            n += 1
+            dt = time.perf_counter() - t0
+            if dt > seconds or n >= 4096:
+                return n, dt, (time.process_time() - c0) / dt
+
+    with threadpool_limits(limits=1):
+        n1, dt1, busy1 = leg(budget_s / 2, 0)
+    nN, dtN, busyN = leg(budget_s / 2, n1)
     return {
-        "value": n * flops_per_token / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
-        "tokens_per_s": n / dt,
-        "sample": f"{n} randomly sampled tokens of {cfg.name}: per-token fp64 forward + analytic backward "
-                  f"(activation/input gradients; weight-gradient outer products not formed), {dt:.1f} s",
+        "value": nN * flops_per_token / dtN / 1e12, "unit": "TFLOP/s", "cores": max(1, int(round(busyN))), "kind": "oracle",
+        "tokens_per_s": nN / dtN, "blas_pool_threads": int(pool), "cores_busy": busyN,
+        "single_thread": {"value": n1 * flops_per_token / dt1 / 1e12, "unit": "TFLOP/s", "tokens_per_s": n1 / dt1,
+                          "cores_busy": busy1},
+        "sample": f"{n1} + {nN} randomly sampled tokens of {cfg.name} (one-thread leg {dt1:.1f} s, then all-thread leg "
+                  f"{dtN:.1f} s; `cores` = process CPU time / wall time of the all-thread leg): per-token fp64 forward + "
+                  f"analytic backward (activation/input gradients; weight-gradient outer products not formed), the "
+                  f"experts' matrices converted to float64 before the clock starts",
     }
 
 
@@ -271,7 +306,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the oracle baseline (0 = skip)")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0, help="budget for the oracle baseline (0 = skip)")
     ap.add_argument("--kernel-reps", type=int, default=20)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB elementwise copy kernel (reference for the HBM byte counters)")
@@ -342,16 +377,35 @@ def main():
     ms_fwd = timed(lambda: smoe.mlp_fwd(X, W1, W2, r, cfg.k, gates, cfg.act, buf), reps)
     ms_bwd = timed(lambda: smoe.mlp_bwd(dY, X, W1, W2, r, cfg.k, gates, cfg.act, buf), reps)
 
-    # dominant kernel: scatter2scatter of the first ParallelLinear (scattered -> grouped), one launch per call
+    # Dominant kernel of the step: the first ParallelLinear (scattered -> grouped).  For bf16 SwiGLU it runs with the
+    # activation in its epilogue; smoe_plinear_act_fwd launches exactly that kernel (and nothing else), writing into
+    # the step's own Hpre / H buffers.  Other activations / fp32: the plain product through smoe_plinear_fwd.
     import ctypes
     rc = r.c()
     d_h = cfg.d_h
     dt_code = smoe.BF16 if cfg.dtype == "bf16" else smoe.F32
+    fused = cfg.act == si.ACT_SWIGLU and cfg.dtype == "bf16" and cfg.d_model % 32 == 0 and cfg.d_model >= 96 and cfg.E <= 256
+    decode = cfg.dtype == "bf16" and cfg.Tk <= 32 * cfg.E and cfg.d_model % 32 == 0
+    static4 = "true" if cfg.d_model % 128 == 0 else "false"
+    if fused:
+        ws_act = smoe._ws(smoe.lib.smoe_plinear_act_fwd_workspace_bytes(dt_code, cfg.act, cfg.T, cfg.k, cfg.d_model,
+                                                                     cfg.d_expert, 1), dev)
 
-    def s2s_once():
-        smoe._check(smoe.lib.smoe_plinear_fwd(smoe.ctx(), stream.cuda_stream, dt_code, X.data_ptr(), cfg.T, cfg.d_model,
-                                              W1.data_ptr(), d_h, ctypes.byref(rc), cfg.k, None, 0, 0, 1,
-                                              buf.Hpre.data_ptr(), None), "smoe_plinear_fwd")
+        def s2s_once():
+            smoe.plinear_act_fwd(X, W1, r, cfg.k, cfg.act, out=(buf.H, buf.Hpre), ws=ws_act)
+
+        kname = (f"s2s_stream_kernel<false,false,1,{static4}> (ParallelLinear #1 scattered->grouped with SwiGLU in its "
+                 "epilogue, as launched inside the step)")
+        if decode:
+            kname = "s2s_decode_kernel<1,false> (ParallelLinear #1 with SwiGLU, small batch)"
+    else:
+        def s2s_once():
+            smoe._check(smoe.lib.smoe_plinear_fwd(smoe.ctx(), stream.cuda_stream, dt_code, X.data_ptr(), cfg.T, cfg.d_model,
+                                                  W1.data_ptr(), d_h, ctypes.byref(rc), cfg.k, None, 0, 0, 1,
+                                                  buf.Hpre.data_ptr(), None), "smoe_plinear_fwd")
+
+        kname = (f"s2s_stream_kernel<false,false,0,{static4}>" if cfg.dtype == "bf16" else "s2s_plain_kernel") + \
+                " (ParallelLinear #1, scattered->grouped)"
 
     ms_s2s = timed(s2s_once, reps)
     s2s_flops = 2.0 * cfg.Tk * cfg.d_model * d_h
@@ -367,29 +421,37 @@ def main():
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"s2s_fwd1_{cfg.name}_hbm_traffic.json")
-    if os.path.exists(tpath):   # HBM bytes per launch measured with rocprofv3 --pmc (see the file for the commands)
+    if os.path.exists(tpath):   # bytes per launch measured with rocprofv3 --pmc (see the file for the commands)
         with open(tpath) as f:
             traffic = json.load(f).get("hbm_bytes_per_launch")
 
-    # The first ParallelLinear is bound by the matrix cores when experts hold hundreds of rows and by HBM
-    # (streaming each used expert's weights once) when they hold a handful, as in the decode workloads.
+    # Algorithmic bytes of that launch: each used expert's W1 once, one gathered X row per routed row, and what the
+    # launch writes (pre-activation, plus H when the activation is fused).
     rows = np.diff(r.expert_offsets.cpu().numpy())
     esz = 2 if cfg.dtype == "bf16" else 4
-    s2s_bytes = float(esz) * (int((rows > 0).sum()) * cfg.d_model * d_h + cfg.Tk * cfg.d_model + cfg.Tk * d_h)
+    used = int((rows > 0).sum())
+    s2s_bytes = float(esz) * (used * cfg.d_model * d_h + cfg.Tk * cfg.d_model + cfg.Tk * d_h +
+                              (cfg.Tk * cfg.d_expert if fused else 0))
     t_mfma, t_hbm = s2s_flops / (peak * 1e12), s2s_bytes / (PEAK_HBM_GBS * 1e9)
-    kname = "s2s_stream_kernel<false,false,0,true> (ParallelLinear #1, scattered->grouped)"
-    if cfg.dtype == "bf16" and cfg.Tk <= 32 * cfg.E and cfg.d_model % 32 == 0:
-        # at most 32 rows per expert on average: the library takes its 32-row-tile kernel; repeated launches
-        # re-read the same weights, part of which the 256 MB memory-side cache may still hold
-        kname = "s2s_decode_kernel<0,false> (ParallelLinear #1, scattered->grouped, small batch)"
-    if t_hbm > t_mfma:
-        gbs = s2s_bytes / (ms_s2s * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": kname, "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": gbs / PEAK_HBM_GBS, "ms_per_launch": ms_s2s, "bytes_per_launch": s2s_bytes,
-                    "traffic": traffic}
-    else:
-        roofline = {"bound": "mfma", "kernel": kname, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                    "frac": achieved / peak, "ms_per_launch": ms_s2s, "flop_per_launch": s2s_flops, "traffic": traffic}
+    gbs = s2s_bytes / (ms_s2s * 1e-3) / 1e9
+    by_hbm = {"bound": "hbm", "kernel": kname, "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+              "frac": gbs / PEAK_HBM_GBS, "ms_per_launch": ms_s2s, "bytes_per_launch": s2s_bytes, "traffic": traffic}
+    by_mfma = {"bound": "mfma", "kernel": kname, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+               "frac": achieved / peak, "ms_per_launch": ms_s2s, "flop_per_launch": s2s_flops, "traffic": traffic}
+    # the roofline that bounds the launch is the one with the longer minimum time; the other one rides along
+    roofline, other = (by_hbm, by_mfma) if t_hbm > t_mfma else (by_mfma, by_hbm)
+    roofline["min_ms_mfma"], roofline["min_ms_hbm"] = t_mfma * 1e3, t_hbm * 1e3
+    roofline["other_roofline"] = {k_: other[k_] for k_ in ("bound", "achieved", "peak", "unit", "frac")}
+
+    # Whole forward pass against HBM: algorithmic bytes with the activation counted as its own pass (each used expert's
+    # W1 and W2 once, gathered X rows, Hpre written and read, H written and read, Yhat written and read, Y written).
+    fwd_bytes = float(esz) * (used * cfg.d_model * (d_h + cfg.d_expert) + cfg.Tk * cfg.d_model + 2 * cfg.Tk * d_h +
+                              2 * cfg.Tk * cfg.d_expert + 2 * cfg.Tk * cfg.d_model + cfg.T * cfg.d_model)
+    fwd_gbs = fwd_bytes / (ms_fwd * 1e-3) / 1e9
+    forward_hbm = {"algorithmic_bytes": fwd_bytes, "ms": ms_fwd, "achieved": fwd_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                   "frac": fwd_gbs / PEAK_HBM_GBS, "min_ms_hbm": fwd_bytes / (PEAK_HBM_GBS * 1e9) * 1e3,
+                   "min_ms_mfma": cfg.gemm_flops_fwd() / (peak * 1e12) * 1e3,
+                   "tflops": cfg.gemm_flops_fwd() / (ms_fwd * 1e-3) / 1e12}
 
     out = {
         "metric": "SMoE MLP fwd+bwd GEMM throughput per layer (routing + Alg. 3 forward + backward)",
@@ -405,10 +467,10 @@ def main():
         "ms_event_p95": float(np.percentile(per_step, 95)),
         "phases_ms": {"routing": ms_route, "mlp_fwd": ms_fwd, "mlp_bwd": ms_bwd},
         "roofline": roofline,
+        "forward_hbm": forward_hbm,
     }
     if args.cpu_seconds > 0:
-        out["cpu_baseline"] = cpu_baseline(case, cfg, gates.cpu().numpy().astype(np.float64), ei.cpu().numpy(),
-                                           args.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(case, cfg, args.cpu_seconds)
     print(json.dumps(out))
 
 

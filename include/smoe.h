@@ -167,6 +167,19 @@ int smoe_plinear_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *
                      const smoe_routing *r, int k, const float *gates, int gates_k, int grouped_in,
                      int grouped_out, void *dX, void *dW, float *dgates, void *ws, size_t ws_bytes);
 
+/* ---- first half of the SMoE MLP: Alg. 3, lines 1-2 ------------------------------------------
+ * H = act(ParallelLinear(X, W1, scattered -> grouped)): the hidden activations of the Tk routed rows in
+ * expert-sorted order, through the same kernels smoe_mlp_fwd uses for them (for bf16 SwiGLU the
+ * activation is applied in the product's epilogue from the fp32 accumulators).
+ *   X [T, d_model];  W1 [E, d_model, d_h], d_h = 2*d_expert for SWIGLU else d_expert;
+ *   Hpre [Tk, d_h] (out, nullable: NULL = the pre-activation is not kept; the workspace then holds it
+ *   for the paths that apply the activation in a second kernel);  H [Tk, d_expert] (out). */
+size_t smoe_plinear_act_fwd_workspace_bytes(smoe_dtype dtype, smoe_act act, int T, int k, int d_model,
+                                            int d_expert, int keep_hpre);
+int smoe_plinear_act_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, const void *X, int T,
+                         int d_model, int d_expert, const void *W1, const smoe_routing *r, int k,
+                         void *Hpre, void *H, void *ws, size_t ws_bytes);
+
 /* ---- SMoE MLP: Alg. 3 -----------------------------------------------------------------
  * Y[t] = sum_j gates[t*k+j] * act(X[t] W1[e]) W2[e]  over the token's k experts (Sec. 3.1
  * step 5), computed as ParallelLinear(scattered->grouped), act, ParallelLinear(grouped->

@@ -23,7 +23,7 @@ EXPORTS = [
     "smoe_create", "smoe_destroy", "smoe_strerror", "smoe_abi_version", "smoe_set_kernel_mode",
     "smoe_topk_gate", "smoe_topk_gate_bwd", "smoe_route_workspace_bytes", "smoe_route", "smoe_route_noalloc",
     "smoe_plinear_fwd", "smoe_plinear_bwd_workspace_bytes", "smoe_plinear_bwd",
-    "smoe_mlp_fwd_workspace_bytes", "smoe_mlp_fwd", "smoe_mlp_bwd_workspace_bytes", "smoe_mlp_bwd",
+    "smoe_plinear_act_fwd_workspace_bytes", "smoe_plinear_act_fwd", "smoe_mlp_fwd_workspace_bytes", "smoe_mlp_fwd", "smoe_mlp_bwd_workspace_bytes", "smoe_mlp_bwd",
     "smoe_group", "smoe_attention_fwd", "smoe_attention_bwd_workspace_bytes", "smoe_attention_bwd",
     "smoe_momha_fwd_workspace_bytes", "smoe_momha_fwd", "smoe_momha_bwd_workspace_bytes", "smoe_momha_bwd",
 ]
@@ -77,6 +77,9 @@ lib.smoe_plinear_bwd_workspace_bytes.argtypes = [_i] * 9
 lib.smoe_plinear_bwd_workspace_bytes.restype = _sz
 lib.smoe_plinear_bwd.argtypes = [_vp, _vp, _i, _vp, _vp, _i, _i, _vp, _i, _vp, _rp, _i, _vp, _i, _i, _i,
                                  _vp, _vp, _vp, _vp, _sz]
+lib.smoe_plinear_act_fwd_workspace_bytes.argtypes = [_i] * 7
+lib.smoe_plinear_act_fwd_workspace_bytes.restype = _sz
+lib.smoe_plinear_act_fwd.argtypes = [_vp, _vp, _i, _i, _vp, _i, _i, _i, _vp, _rp, _i, _vp, _vp, _vp, _sz]
 lib.smoe_mlp_fwd_workspace_bytes.argtypes = [_i] * 7
 lib.smoe_mlp_fwd_workspace_bytes.restype = _sz
 lib.smoe_mlp_fwd.argtypes = [_vp, _vp, _i, _i, _vp, _i, _i, _i, _vp, _vp, _rp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _sz]
@@ -337,6 +340,26 @@ def plinear_bwd(dY, X, W, Yhat, r: Routing, k: int, gates=None, grouped_in=False
 
 def hidden_width(act: int, d_expert: int) -> int:
     return 2 * d_expert if act == ACT_SWIGLU else d_expert
+
+
+def plinear_act_fwd(X, W1, r: Routing, k: int, act: int, keep_hpre=True, out=None, ws=None):
+    """Alg. 3 lines 1-2: returns (H, Hpre or None) in expert-sorted order.  `out` = (H, Hpre) and `ws` reuse
+    preallocated tensors (repeated calls then allocate nothing)."""
+    _chk(X); _chk(W1, X.dtype)
+    T, d_model = X.shape
+    d_expert = W1.shape[2] // 2 if act == ACT_SWIGLU else W1.shape[2]
+    if out is None:
+        H = _new(r.Tk, d_expert, dtype=X.dtype, device=X.device)
+        Hpre = _new(r.Tk, W1.shape[2], dtype=X.dtype, device=X.device) if keep_hpre else None
+    else:
+        H, Hpre = out
+    nb = lib.smoe_plinear_act_fwd_workspace_bytes(_dt(X), act, T, k, d_model, d_expert, int(Hpre is not None))
+    if ws is None:
+        ws = _ws(nb, X.device)
+    rc = r.c()
+    _check(lib.smoe_plinear_act_fwd(ctx(), _stream(), _dt(X), act, _p(X), T, d_model, d_expert, _p(W1), ctypes.byref(rc), k,
+                                    _p(Hpre), _p(H), _p(ws), ws.numel()), "smoe_plinear_act_fwd")
+    return H, Hpre
 
 
 class MLPBuffers:

@@ -313,6 +313,55 @@ int smoe_plinear_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, const void *
 // ------------------------------------------------------------------------------ Alg. 3
 static inline int hidden_width(smoe_act act, int d_expert) { return act == SMOE_ACT_SWIGLU ? 2 * d_expert : d_expert; }
 
+// Hpre = ParallelLinear(X, W1, scattered -> grouped);  H = sigma(Hpre)   (first two lines of Alg. 3).
+// Hpre always points at room for the pre-activation; keep_hpre says whether the caller wants it written
+// (when the activation is applied in the product's epilogue it is otherwise never stored).
+static int hidden_forward(smoe_ctx *ctx, hipStream_t s, smoe_dtype dtype, smoe_act act, const void *X, int d_model,
+                          int d_expert, const void *W1, const smoe_routing *r, int k, void *Hpre, bool keep_hpre, void *H,
+                          float *tail_ws) {
+  const int d_h = hidden_width(act, d_expert);
+  S2SArgs a1 = make_s2s(X, W1, Hpre, r, d_model, d_h, false, false, k, true);
+  a1.tail_ws = tail_ws;
+  S2SArgs fused = a1;
+  fused.H = H;
+  fused.grid = ctx->stream_grid;
+  if (act == SMOE_ACT_SWIGLU && dtype == SMOE_BF16 && ctx->kernel_mode == 0 &&
+      (s2s_decode_supported(fused) || s2s_stream_swiglu_supported(fused))) {
+    // SwiGLU in the product's epilogue: H comes straight from the fp32 accumulators, and the
+    // pre-activation is written only when the caller keeps it for the backward pass
+    if (!keep_hpre) fused.C = nullptr;
+    return s2s_decode_supported(fused) ? launch_s2s_decode(s, fused) : launch_s2s_stream(s, fused);
+  }
+  int rc = run_s2s(ctx, s, dtype, a1);
+  if (rc != SMOE_OK) return rc;
+  return launch_act_fwd(s, dtype, act, Hpre, H, r->Tk, d_expert);
+}
+
+size_t smoe_plinear_act_fwd_workspace_bytes(smoe_dtype dtype, smoe_act act, int T, int k, int d_model, int d_expert,
+                                            int keep_hpre) {
+  if (!dtype_ok(dtype) || T < 0 || k < 1 || d_model < 1 || d_expert < 1) return 0;
+  size_t hpre = keep_hpre ? 0 : align256((size_t)T * k * hidden_width(act, d_expert) * dtype_size(dtype));
+  return hpre + S2S_TAIL_WS_BYTES;
+}
+
+int smoe_plinear_act_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, const void *X, int T, int d_model,
+                         int d_expert, const void *W1, const smoe_routing *r, int k, void *Hpre, void *H, void *ws,
+                         size_t ws_bytes) {
+  if (!ctx || !dtype_ok(dtype) || !routing_ok(r) || T < 0 || k < 1 || d_model < 1 || d_expert < 1)
+    return SMOE_ERR_INVALID_ARG;
+  if (act != SMOE_ACT_NONE && act != SMOE_ACT_GELU && act != SMOE_ACT_SWIGLU) return SMOE_ERR_INVALID_ARG;
+  if ((long long)T * k != r->Tk) return SMOE_ERR_INVALID_ARG;
+  if (T == 0) return SMOE_OK;
+  if (!X || !W1 || !H) return SMOE_ERR_INVALID_ARG;
+  if (!width_ok(dtype, d_model) || !width_ok(dtype, d_expert)) return SMOE_ERR_UNSUPPORTED;
+  size_t need = smoe_plinear_act_fwd_workspace_bytes(dtype, act, T, k, d_model, d_expert, Hpre != nullptr);
+  if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need) return SMOE_ERR_WORKSPACE;
+  float *tail_ws = (float *)((char *)ws + need - S2S_TAIL_WS_BYTES);
+  void *pre = Hpre ? Hpre : ws;
+  if (!aligned16(X) || !aligned16(W1) || !aligned16(H) || !aligned16(pre)) return SMOE_ERR_UNSUPPORTED;
+  return hidden_forward(ctx, (hipStream_t)stream, dtype, act, X, d_model, d_expert, W1, r, k, pre, Hpre != nullptr, H, tail_ws);
+}
+
 size_t smoe_mlp_fwd_workspace_bytes(smoe_dtype dtype, smoe_act act, int T, int k, int d_model, int d_expert,
                                     int training) {
   if (!dtype_ok(dtype) || T < 0 || k < 1 || d_model < 1 || d_expert < 1) return 0;
@@ -348,26 +397,8 @@ int smoe_mlp_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
       !aligned16(saved_H) || !aligned16(saved_Yhat))
     return SMOE_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
-  // Hpre = ParallelLinear(X, W1, scattered -> grouped);  H = sigma(Hpre)
-  S2SArgs a1 = make_s2s(X, W1, saved_Hpre, r, d_model, d_h, false, false, k, true);
-  a1.tail_ws = tail_ws;
-  int rc;
-  S2SArgs fused = a1;
-  fused.H = saved_H;
-  fused.grid = ctx->stream_grid;
-  if (act == SMOE_ACT_SWIGLU && dtype == SMOE_BF16 && ctx->kernel_mode == 0 &&
-      (s2s_decode_supported(fused) || s2s_stream_swiglu_supported(fused))) {
-    // SwiGLU in the product's epilogue: H comes straight from the fp32 accumulators, and the
-    // pre-activation is written only when the caller keeps it for the backward pass
-    if (nsaved == 0) fused.C = nullptr;
-    rc = s2s_decode_supported(fused) ? launch_s2s_decode(s, fused) : launch_s2s_stream(s, fused);
-    if (rc != SMOE_OK) return rc;
-  } else {
-    rc = run_s2s(ctx, s, dtype, a1);
-    if (rc != SMOE_OK) return rc;
-    rc = launch_act_fwd(s, dtype, act, saved_Hpre, saved_H, Tk, d_expert);
-    if (rc != SMOE_OK) return rc;
-  }
+  int rc = hidden_forward(ctx, s, dtype, act, X, d_model, d_expert, W1, r, k, saved_Hpre, nsaved != 0, saved_H, tail_ws);
+  if (rc != SMOE_OK) return rc;
   // Y = ParallelLinear(H, W2, p, grouped -> scattered)
   S2SArgs a2 = make_s2s(saved_H, W2, saved_Yhat, r, d_expert, d_model, false, true, 1, false);
   a2.tail_ws = tail_ws;

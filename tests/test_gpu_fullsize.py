@@ -32,9 +32,12 @@ def smoe():
 
 
 class ExpertCache:
-    """float64 views of a few experts' matrices (conversion is the slow part of a sampled check)."""
+    """float64 views of the experts' matrices (conversion is the slow part of a sampled check): all of them
+    when they fit a few GB, else the most recent two."""
 
-    def __init__(self, w32: np.ndarray, keep: int = 2):
+    def __init__(self, w32: np.ndarray, keep: int | None = None):
+        if keep is None:
+            keep = w32.shape[0] if w32.size * 8 <= 12e9 else 2
         self.w, self.keep, self.cache, self.shape = w32, keep, {}, w32.shape
 
     def __getitem__(self, e):
@@ -46,15 +49,36 @@ class ExpertCache:
         return self.cache[e]
 
 
-def _sample_tokens(ei, E, per_expert, seed):
-    """Tokens covering every non-empty expert (rarest included), ordered by expert pair for cache reuse."""
+def _sample_tokens(ei, E, per_expert, seed, o, off, k):
+    """Tokens covering every non-empty expert (rarest included), ordered by expert pair for cache reuse.  The
+    routed rows are taken from the first, a middle and the last (usually ragged) 256-row tile of every
+    expert's segment in equal shares, so that every position of a persistent block's tile list is visited."""
     rng = np.random.default_rng(seed)
     chosen = set()
     for e in range(E):
-        toks = np.nonzero((ei == e).any(axis=1))[0]
-        if len(toks):
-            chosen.update(rng.choice(toks, size=min(per_expert, len(toks)), replace=False).tolist())
+        lo, hi = int(off[e]), int(off[e + 1])
+        if hi == lo:
+            continue
+        tiles = (hi - lo + 255) // 256
+        picks = sorted({0, tiles // 2, tiles - 1})
+        for n, tile in enumerate(picks):
+            a, b = lo + tile * 256, min(lo + tile * 256 + 256, hi)
+            want = max(per_expert // len(picks) + (1 if n < per_expert % len(picks) else 0), 1)
+            here = o[a:b] // k
+            have = sum(1 for t in here.tolist() if t in chosen)      # tokens picked for other experts count too
+            fresh = np.asarray([t for t in here.tolist() if t not in chosen], dtype=np.int64)
+            if want > have and len(fresh):
+                chosen.update(rng.choice(fresh, size=min(want - have, len(fresh)), replace=False).tolist())
     return sorted(chosen, key=lambda t: tuple(sorted(ei[t].tolist())))
+
+
+def _sample_units(d_expert, n, rng):
+    """n hidden units from n different 256-wide column tiles (all of them when there are fewer tiles)."""
+    tiles = (d_expert + 255) // 256
+    units = []
+    for t in rng.choice(tiles, size=min(n, tiles), replace=False):
+        units.append(int(rng.integers(t * 256, min(t * 256 + 256, d_expert))))
+    return np.asarray(sorted(units), dtype=np.int64)
 
 
 def _check(name, gpu, ref, tol, scale=None, rows=True):
@@ -101,7 +125,7 @@ def _run_fullsize(smoe, cfg, seed, tokens_per_expert, dw_samples, backward=True,
     dY32 = si.as_f32(case["dY"]) if backward else None
     inv = np.empty(cfg.Tk, dtype=np.int64)
     inv[o] = np.arange(cfg.Tk)                     # sorted position of every slot
-    toks = _sample_tokens(ei, cfg.E, tokens_per_expert, seed)
+    toks = _sample_tokens(ei, cfg.E, tokens_per_expert, seed, o, off, cfg.k)
     if last_rows:
         # tokens with a slot among the last expert-sorted rows: the output tiles the persistent kernels reach
         # last, where a partly filled last round has its contraction split over several blocks
@@ -138,7 +162,7 @@ def _run_fullsize(smoe, cfg, seed, tokens_per_expert, dw_samples, backward=True,
         rng = np.random.default_rng(seed + 1)
         r2, g2, r1, g1 = [], [], [], []
         for e in range(cfg.E):
-            units = rng.choice(cfg.d_expert, size=dw_samples, replace=False)
+            units = _sample_units(cfg.d_expert, dw_samples, rng)
             ref2 = oracle.mlp_dW2_rows(dY32, X32, W1c, W2c, ei, g64, cfg.act, e, units)
             got2 = dW2[e][torch.from_numpy(units).cuda()].float().cpu().numpy().astype(np.float64)
             ref1 = oracle.mlp_dW1_cols(dY32, X32, W1c, W2c, ei, g64, cfg.act, e, units)
@@ -157,11 +181,11 @@ def _run_fullsize(smoe, cfg, seed, tokens_per_expert, dw_samples, backward=True,
 
 
 def test_C2_small_bf16_sampled(smoe):
-    _run_fullsize(smoe, si.CONFIGS["C2"], 0, tokens_per_expert=4, dw_samples=2)
+    _run_fullsize(smoe, si.CONFIGS["C2"], 0, tokens_per_expert=6, dw_samples=4)
 
 
 def test_C3_mixtral_layer_sampled(smoe):
-    _run_fullsize(smoe, si.CONFIGS["C3"], 0, tokens_per_expert=2, dw_samples=1, last_rows=512)
+    _run_fullsize(smoe, si.CONFIGS["C3"], 0, tokens_per_expert=8, dw_samples=8, last_rows=512)
 
 
 @pytest.mark.parametrize("d_model,d_expert", [(3072, 2816), (3104, 2848)])
@@ -192,14 +216,14 @@ def test_partial_last_round_split_sampled(smoe, d_model, d_expert):
 
 
 def test_C4_granular_sampled(smoe):
-    _run_fullsize(smoe, si.CONFIGS["C4"], 0, tokens_per_expert=1, dw_samples=1)
+    _run_fullsize(smoe, si.CONFIGS["C4"], 0, tokens_per_expert=4, dw_samples=2)
 
 
 @pytest.mark.parametrize("name", ["G4", "G16"])
 def test_unit_benchmark_shapes_sampled(smoe, name):
     """Sec. 4.1 / 4.2 shapes (d_model 4096, d_expert = 8192/k, E = 8k, 61440 tokens): the headline k = 4 and the
     finest granularity k = 16 (128 experts, 983040 routed rows)."""
-    _run_fullsize(smoe, si.CONFIGS[name], 0, tokens_per_expert=1, dw_samples=1)
+    _run_fullsize(smoe, si.CONFIGS[name], 0, tokens_per_expert=4, dw_samples=2)
 
 
 @pytest.mark.parametrize("name", ["C4-decode", "C4-decode-masked"])

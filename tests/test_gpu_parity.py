@@ -337,6 +337,24 @@ def test_mlp_inference_mode_matches_training_forward(smoe, name):
     assert_close(Yi, ref["Y"], torch_dtype(cfg.dtype), f"{name} inference Y")
 
 
+@pytest.mark.parametrize("name", ["C1", "C3-small", "C3-small-f32"])
+def test_hidden_activations_entry_point(smoe, name):
+    """smoe_plinear_act_fwd (Alg. 3 lines 1-2) against the oracle, with and without keeping the pre-activation."""
+    cfg = si.CONFIGS[name]
+    case = si.mlp_case(cfg, 4)
+    gi, gg = smoe.topk_gate(case["logits"].cuda(), cfg.k)
+    r = smoe.route(gi, cfg.E)
+    ei, g, se, o, off = oracle_routing(case["logits"], cfg.k, cfg.E)
+    X, W1 = case["X"].cuda(), case["W1"].cuda()
+    H, Hpre = smoe.plinear_act_fwd(X, W1, r, cfg.k, cfg.act, keep_hpre=True)
+    H2, none = smoe.plinear_act_fwd(X, W1, r, cfg.k, cfg.act, keep_hpre=False)
+    assert none is None and torch.equal(H, H2)
+    ref = oracle.mlp_fwd(si.as_f64(case["X"]), si.as_f64(case["W1"]), si.as_f64(case["W2"]), ei, oracle_gates_f32(g), cfg.act)
+    td = torch_dtype(cfg.dtype)
+    assert_close(Hpre, ref["Hpre"][o], td, "Hpre (grouped)")
+    assert_close(H, ref["H"][o], td, "H (grouped)")
+
+
 def test_mlp_empty_batch(smoe):
     cfg = si.CONFIGS["C1"]
     case = si.mlp_case(cfg, 0)
