@@ -187,19 +187,29 @@ int smoe_plinear_act_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act
  *   X [T, d_model];  W1 [E, d_model, d_h] with d_h = 2*d_expert for SWIGLU else d_expert;
  *   W2 [E, d_expert, d_model];  gates [T*k] fp32;  Y [T, d_model] (out).
  *   saved_Hpre [Tk, d_h], saved_H [Tk, d_expert] (expert-sorted order) and saved_Yhat
- *   [Tk, d_model] (slot order): outputs kept for the backward pass.  Pass all three or
- *   none; with none (inference) the workspace holds them instead.  In both modes the
- *   workspace also holds the 64 MiB of partial tiles of a split last round (see
- *   smoe_plinear_bwd), so it is never empty. */
+ *   [Tk, d_model] (slot order): outputs kept for the backward pass.  Pass saved_Hpre and
+ *   saved_H together or neither (inference: the workspace holds everything).  saved_Yhat
+ *   (the unweighted second product, Alg. 2's input for dp) is needed by smoe_mlp_bwd only
+ *   when smoe_mlp_saves_yhat says so; it may be NULL otherwise, and the workspace then holds
+ *   it for the duration of the call.  `training` of the workspace query: 0 = nothing saved,
+ *   1 = all three saved, 2 = Hpre and H saved, Yhat not.  The workspace always includes the
+ *   64 MiB of partial tiles of a split last round (see smoe_plinear_bwd). */
 size_t smoe_mlp_fwd_workspace_bytes(smoe_dtype dtype, smoe_act act, int T, int k, int d_model,
                                     int d_expert, int training);
+/* 1 if smoe_mlp_bwd of this shape reads the forward's saved_Yhat, 0 if it does not (bf16 SwiGLU
+ * shapes the persistent kernels take: dp[t,j] = <dY_t W2[e]^T, H_i> is then formed in the epilogue of
+ * the W2^T product from its fp32 accumulators, in the spirit of Sec. 3.2.1's buffer reuse, and the
+ * activation's derivative is applied there too), negative smoe_status on bad arguments. */
+int smoe_mlp_saves_yhat(smoe_ctx *ctx, smoe_dtype dtype, smoe_act act, int T, int k, int E, int d_model,
+                        int d_expert);
 int smoe_mlp_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, const void *X, int T,
                  int d_model, int d_expert, const void *W1, const void *W2, const smoe_routing *r,
                  int k, const float *gates, void *Y, void *saved_Hpre, void *saved_H,
                  void *saved_Yhat, void *ws, size_t ws_bytes);
 
 /* Backward of smoe_mlp_fwd (Alg. 2 applied to both ParallelLinears, one `group` each).
- *   dY [T, d_model] upstream gradient; saved_* from the forward call.
+ *   dY [T, d_model] upstream gradient; saved_* from the forward call (saved_Yhat may be NULL
+ *   when smoe_mlp_saves_yhat returns 0).
  *   dX [T, d_model], dW1 like W1, dW2 like W2, dgates [T*k] fp32 (all out, none nullable). */
 size_t smoe_mlp_bwd_workspace_bytes(smoe_dtype dtype, smoe_act act, int T, int k, int d_model,
                                     int d_expert);

@@ -23,7 +23,7 @@ EXPORTS = [
     "smoe_create", "smoe_destroy", "smoe_strerror", "smoe_abi_version", "smoe_set_kernel_mode",
     "smoe_topk_gate", "smoe_topk_gate_bwd", "smoe_route_workspace_bytes", "smoe_route", "smoe_route_noalloc",
     "smoe_plinear_fwd", "smoe_plinear_bwd_workspace_bytes", "smoe_plinear_bwd",
-    "smoe_plinear_act_fwd_workspace_bytes", "smoe_plinear_act_fwd", "smoe_mlp_fwd_workspace_bytes", "smoe_mlp_fwd", "smoe_mlp_bwd_workspace_bytes", "smoe_mlp_bwd",
+    "smoe_plinear_act_fwd_workspace_bytes", "smoe_plinear_act_fwd", "smoe_mlp_fwd_workspace_bytes", "smoe_mlp_fwd", "smoe_mlp_saves_yhat", "smoe_mlp_bwd_workspace_bytes", "smoe_mlp_bwd",
     "smoe_group", "smoe_attention_fwd", "smoe_attention_bwd_workspace_bytes", "smoe_attention_bwd",
     "smoe_momha_fwd_workspace_bytes", "smoe_momha_fwd", "smoe_momha_bwd_workspace_bytes", "smoe_momha_bwd",
 ]
@@ -84,6 +84,7 @@ lib.smoe_mlp_fwd_workspace_bytes.argtypes = [_i] * 7
 lib.smoe_mlp_fwd_workspace_bytes.restype = _sz
 lib.smoe_mlp_fwd.argtypes = [_vp, _vp, _i, _i, _vp, _i, _i, _i, _vp, _vp, _rp, _i, _vp, _vp, _vp, _vp, _vp, _vp, _sz]
 lib.smoe_mlp_bwd_workspace_bytes.argtypes = [_i] * 6
+lib.smoe_mlp_saves_yhat.argtypes = [_vp, _i, _i, _i, _i, _i, _i, _i]
 lib.smoe_mlp_bwd_workspace_bytes.restype = _sz
 lib.smoe_mlp_bwd.argtypes = [_vp, _vp, _i, _i, _vp, _vp, _i, _i, _i, _vp, _vp, _rp, _i, _vp, _vp, _vp, _vp,
                              _vp, _vp, _vp, _vp, _vp, _sz]
@@ -373,14 +374,19 @@ class MLPBuffers:
         self.T, self.k, self.E, self.d_model, self.d_expert, self.act, self.dtype = T, k, E, d_model, d_expert, act, dtype
         self.Y = mk(T, d_model)
         self.training = training
+        mode = 0
         if training:
-            self.Hpre, self.H, self.Yhat = mk(Tk, d_h), mk(Tk, d_expert), mk(Tk, d_model)
+            needs = lib.smoe_mlp_saves_yhat(ctx(), dt, act, T, k, E, d_model, d_expert)
+            _check(min(needs, 0), "smoe_mlp_saves_yhat")
+            mode = 1 if needs else 2
+            # the unweighted second product is kept only when the backward pass of this shape reads it
+            self.Hpre, self.H, self.Yhat = mk(Tk, d_h), mk(Tk, d_expert), (mk(Tk, d_model) if needs else None)
             self.dX, self.dW1, self.dW2 = mk(T, d_model), mk(E, d_model, d_h), mk(E, d_expert, d_model)
             self.dgates = _new(T, k, dtype=torch.float32, device=device)
             self.ws_bwd = _ws(lib.smoe_mlp_bwd_workspace_bytes(dt, act, T, k, d_model, d_expert), device)
         else:
             self.Hpre = self.H = self.Yhat = None
-        self.ws_fwd = _ws(lib.smoe_mlp_fwd_workspace_bytes(dt, act, T, k, d_model, d_expert, int(training)), device)
+        self.ws_fwd = _ws(lib.smoe_mlp_fwd_workspace_bytes(dt, act, T, k, d_model, d_expert, mode), device)
 
 
 def mlp_fwd(X, W1, W2, r: Routing, k: int, gates, act: int, buf: MLPBuffers | None = None, training=True):

@@ -365,8 +365,9 @@ int smoe_plinear_act_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act
 size_t smoe_mlp_fwd_workspace_bytes(smoe_dtype dtype, smoe_act act, int T, int k, int d_model, int d_expert,
                                     int training) {
   if (!dtype_ok(dtype) || T < 0 || k < 1 || d_model < 1 || d_expert < 1) return 0;
-  if (training) return S2S_TAIL_WS_BYTES;
   size_t es = dtype_size(dtype), Tk = (size_t)T * k;
+  if (training == 1) return S2S_TAIL_WS_BYTES;
+  if (training == 2) return align256(Tk * d_model * es) + S2S_TAIL_WS_BYTES;      // Hpre and H kept, Yhat lives here
   return align256(Tk * hidden_width(act, d_expert) * es) + align256(Tk * d_expert * es) +
          align256(Tk * d_model * es) + S2S_TAIL_WS_BYTES;
 }
@@ -378,16 +379,19 @@ int smoe_mlp_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
     return SMOE_ERR_INVALID_ARG;
   if (act != SMOE_ACT_NONE && act != SMOE_ACT_GELU && act != SMOE_ACT_SWIGLU) return SMOE_ERR_INVALID_ARG;
   if ((long long)T * k != r->Tk) return SMOE_ERR_INVALID_ARG;
-  int nsaved = (saved_Hpre != nullptr) + (saved_H != nullptr) + (saved_Yhat != nullptr);
-  if (nsaved != 0 && nsaved != 3) return SMOE_ERR_INVALID_ARG;
+  const int nhid = (saved_Hpre != nullptr) + (saved_H != nullptr);
+  if (nhid == 1 || (nhid == 0 && saved_Yhat)) return SMOE_ERR_INVALID_ARG;
+  const int nsaved = nhid ? 3 : 0;                      // 3: training (Yhat may still live in the workspace)
+  const int mode = nhid == 0 ? 0 : (saved_Yhat ? 1 : 2);
   if (T == 0) return SMOE_OK;
   if (!X || !W1 || !W2 || !gates || !Y) return SMOE_ERR_INVALID_ARG;
   const int d_h = hidden_width(act, d_expert), Tk = r->Tk;
   if (!width_ok(dtype, d_model) || !width_ok(dtype, d_expert)) return SMOE_ERR_UNSUPPORTED;
   size_t es = dtype_size(dtype);
-  size_t need = smoe_mlp_fwd_workspace_bytes(dtype, act, T, k, d_model, d_expert, nsaved != 0);
+  size_t need = smoe_mlp_fwd_workspace_bytes(dtype, act, T, k, d_model, d_expert, mode);
   if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need) return SMOE_ERR_WORKSPACE;
   float *tail_ws = (float *)((char *)ws + need - S2S_TAIL_WS_BYTES);   // partial tiles of a split last round
+  if (mode == 2) saved_Yhat = ws;
   if (nsaved == 0) {
     saved_Hpre = ws;
     saved_H = (char *)saved_Hpre + align256((size_t)Tk * d_h * es);
@@ -409,11 +413,54 @@ int smoe_mlp_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
 
 // Workspace of the backward pass: dYbar [Tk,d_model] (later reused for dXbar), dH [Tk,d_expert],
 // dHpre [Tk,d_h].
+// Fused layout (bf16 SwiGLU through the persistent kernels): the unweighted and the weighted expert-sorted copies of
+// dY [Tk,d_model] each (the first one later holds Xbar, then dXbar), dHpre [Tk,d_h], the sorted routing weights [Tk]
+// and the slabs of dp [Tk, 2 * ceil(d_expert / 256)] fp32.
+struct MlpBwdFusedLayout {
+  size_t dybar_u, dybar_w, dhpre, gsorted, dp_part, total;
+  int part_ld;
+};
+static MlpBwdFusedLayout mlp_bwd_fused_layout(size_t es, size_t Tk, int d_model, int d_expert) {
+  MlpBwdFusedLayout L;
+  size_t off = 0;
+  L.part_ld = 2 * ceil_div(d_expert, 256);
+  L.dybar_u = off;  off += align256(Tk * d_model * es);
+  L.dybar_w = off;  off += align256(Tk * d_model * es);
+  L.dhpre = off;    off += align256(Tk * 2 * (size_t)d_expert * es);
+  L.gsorted = off;  off += align256(Tk * sizeof(float));
+  L.dp_part = off;  off += align256(Tk * (size_t)L.part_ld * sizeof(float));
+  L.total = off + S2S_TAIL_WS_BYTES;
+  return L;
+}
+
 size_t smoe_mlp_bwd_workspace_bytes(smoe_dtype dtype, smoe_act act, int T, int k, int d_model, int d_expert) {
   if (!dtype_ok(dtype) || T < 0 || k < 1 || d_model < 1 || d_expert < 1) return 0;
   size_t es = dtype_size(dtype), Tk = (size_t)T * k;
-  return align256(Tk * d_model * es) + align256(Tk * d_expert * es) + align256(Tk * hidden_width(act, d_expert) * es) +
-         S2S_TAIL_WS_BYTES;
+  size_t plain = align256(Tk * d_model * es) + align256(Tk * d_expert * es) + align256(Tk * hidden_width(act, d_expert) * es) +
+                 S2S_TAIL_WS_BYTES;
+  if (dtype != SMOE_BF16 || act != SMOE_ACT_SWIGLU) return plain;
+  size_t fused = mlp_bwd_fused_layout(es, Tk, d_model, d_expert).total;   // whichever path the shape takes fits
+  return fused > plain ? fused : plain;
+}
+
+// Whether the backward pass of this shape computes dp in the input-gradient product's epilogue, so that the forward's
+// unweighted Yhat need not be kept for it.
+static bool mlp_bwd_fused(const smoe_ctx *ctx, smoe_dtype dtype, smoe_act act, int Tk, int E, int d_model, int d_expert) {
+  if (dtype != SMOE_BF16 || act != SMOE_ACT_SWIGLU || ctx->kernel_mode != 0 || Tk < 1) return false;
+  S2SArgs x;
+  x.A = x.W = nullptr;  x.C = nullptr;
+  x.a_map = RowMap{nullptr, 1};  x.c_map = RowMap{nullptr, 1};
+  x.offsets = nullptr;  x.E = E;  x.Tk = Tk;
+  x.K = d_model;  x.N = d_expert;  x.ldw = d_model;  x.w_stride = (size_t)d_expert * d_model;  x.trans_w = 1;
+  x.tail_ws = nullptr;  x.H = nullptr;
+  x.grid = ctx->stream_grid;
+  x.Hpre_in = (const void *)1;  x.row_scale = (const float *)1;  x.dp_part = (float *)1;   // only tested for presence
+  return s2s_stream_swiglu_bwd_supported(x);
+}
+
+int smoe_mlp_saves_yhat(smoe_ctx *ctx, smoe_dtype dtype, smoe_act act, int T, int k, int E, int d_model, int d_expert) {
+  if (!ctx || !dtype_ok(dtype) || T < 0 || k < 1 || E < 1 || d_model < 1 || d_expert < 1) return SMOE_ERR_INVALID_ARG;
+  return mlp_bwd_fused(ctx, dtype, act, T * k, E, d_model, d_expert) ? 0 : 1;
 }
 
 int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, const void *dY, const void *X, int T,
@@ -439,11 +486,50 @@ int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
     DWArgs z2{nullptr, nullptr, dW2, r->expert_offsets, r->E, 0, d_expert, d_model};
     return launch_dw_plain(s, dtype, z2);
   }
-  if (!dY || !X || !W1 || !W2 || !gates || !saved_Hpre || !saved_H || !saved_Yhat || !dX || !dgates)
+  const bool fused = mlp_bwd_fused(ctx, dtype, act, Tk, r->E, d_model, d_expert);
+  if (!dY || !X || !W1 || !W2 || !gates || !saved_Hpre || !saved_H || (!saved_Yhat && !fused) || !dX || !dgates)
     return SMOE_ERR_INVALID_ARG;
   if (!aligned16(dY) || !aligned16(X) || !aligned16(W1) || !aligned16(W2) || !aligned16(saved_Hpre) ||
-      !aligned16(saved_H) || !aligned16(saved_Yhat) || !aligned16(dX) || !aligned16(dW1) || !aligned16(dW2))
+      !aligned16(saved_H) || (saved_Yhat && !aligned16(saved_Yhat)) || !aligned16(dX) || !aligned16(dW1) || !aligned16(dW2))
     return SMOE_ERR_UNSUPPORTED;
+  if (fused) {
+    // Alg. 2 for both ParallelLinears with the activation's derivative and dp taken in the epilogue of the
+    // W2^T product: that product runs on the UNWEIGHTED sorted copy of dY, so its fp32 accumulators are dH / p and
+    // dp[row] = <acc, H[row]> needs neither the forward's Yhat nor a division by a routing weight; groupXTY for dW2
+    // takes the weighted copy.
+    const MlpBwdFusedLayout L = mlp_bwd_fused_layout(es, (size_t)Tk, d_model, d_expert);
+    char *base = (char *)ws;
+    void *dYu = base + L.dybar_u, *dYw = base + L.dybar_w, *dHpre = base + L.dhpre;
+    float *gsorted = (float *)(base + L.gsorted), *dp_part = (float *)(base + L.dp_part);
+    float *tail_ws = (float *)(base + L.total - S2S_TAIL_WS_BYTES);
+    rc = launch_group_pair(s, dtype, dY, r->sorted_scattered_idxs, k, gates, dYu, dYw, gsorted, Tk, d_model);
+    if (rc != SMOE_OK) return rc;
+    S2SArgs x2 = make_s2s(dYu, W2, dHpre, r, d_expert, d_model, true, true, 1, true);   // dHpre = sigma'(Hpre) p (dYu W2^T)
+    x2.Hpre_in = saved_Hpre;
+    x2.row_scale = gsorted;
+    x2.dp_part = dp_part;
+    x2.grid = ctx->stream_grid;
+    rc = launch_s2s_stream(s, x2);
+    if (rc != SMOE_OK) return rc;
+    rc = launch_dp_reduce(s, dp_part, L.part_ld, r->sorted_scattered_idxs, dgates, Tk);
+    if (rc != SMOE_OK) return rc;
+    DWArgs w2{saved_H, dYw, dW2, r->expert_offsets, r->E, Tk, d_expert, d_model};
+    w2.split_ws = tail_ws;
+    rc = run_dw(ctx, s, dtype, w2);
+    if (rc != SMOE_OK) return rc;
+    void *Xbar = dYu;                                    // dYu is dead: its array holds Xbar, then dXbar
+    rc = launch_group(s, dtype, X, r->sorted_scattered_idxs, k, nullptr, Xbar, Tk, d_model);
+    if (rc != SMOE_OK) return rc;
+    DWArgs w1{Xbar, dHpre, dW1, r->expert_offsets, r->E, Tk, d_model, d_h};
+    w1.split_ws = tail_ws;
+    rc = run_dw(ctx, s, dtype, w1);
+    if (rc != SMOE_OK) return rc;
+    S2SArgs x1 = make_s2s(dHpre, W1, k == 1 ? dX : Xbar, r, d_model, d_h, true, true, 1, false);
+    x1.tail_ws = tail_ws;
+    rc = run_s2s(ctx, s, dtype, x1);
+    if (rc != SMOE_OK || k == 1) return rc;
+    return launch_combine(s, dtype, Xbar, nullptr, dX, T, k, d_model);
+  }
   char *p = (char *)ws;
   void *dYbar = p;                 p += align256((size_t)Tk * d_model * es);
   void *dH = p;                    p += align256((size_t)Tk * d_expert * es);

@@ -69,6 +69,13 @@ int launch_act_bwd(hipStream_t s, smoe_dtype dt, smoe_act act, const void *Hpre,
 int launch_combine(hipStream_t s, smoe_dtype dt, const void *Yhat, const float *g, void *Y, int T, int k, int d);
 int launch_group(hipStream_t s, smoe_dtype dt, const void *in, const int32_t *o, int fan, const float *g,
                  void *out, int Tk, int d);
+// One pass over `in` for Alg. 2's weight-and-group step when both forms are needed: out_plain[i] = in[o[i] / fan],
+// out_weighted[i] = g[o[i]] * in[o[i] / fan], g_sorted[i] = g[o[i]].
+int launch_group_pair(hipStream_t s, smoe_dtype dt, const void *in, const int32_t *o, int fan, const float *g,
+                      void *out_plain, void *out_weighted, float *g_sorted, int Tk, int d);
+// dg[o[i]] = sum_c part[i, c] (c ascending): finishes the routing-weight gradient left in slabs by the fused
+// SwiGLU backward epilogue.
+int launch_dp_reduce(hipStream_t s, const float *part, int ld, const int32_t *o, float *dg, int Tk);
 // dg[s] = <dY[s / kp], Yhat[s]>
 int launch_rowdot(hipStream_t s, smoe_dtype dt, const void *dY, const void *Yhat, float *dg, int Tk, int kp, int d);
 
@@ -92,6 +99,15 @@ struct S2SArgs {      // C[out(i), :] = A[in(i), :] * op(W[e(i)])   for sorted r
   // [gate | up] halves of width N / 2 and H [*, N / 2] receives silu(gate) * up; C may then be
   // NULL when the pre-activation is not kept.
   void *H;
+  // Optional fused SwiGLU backward of Alg. 3 (input-gradient product of the second ParallelLinear, expert-sorted
+  // in and out, op(W) = W^T, N = d_expert): A holds the UNWEIGHTED expert-sorted upstream rows, so the fp32
+  // accumulators are dH / p.  With Hpre_in [Tk, 2N] (the saved pre-activation), row_scale [Tk] (the routing
+  // weight of every sorted row) and dp_part [Tk, 2 * ceil(N / 256)] fp32 set, the epilogue writes
+  // C = dHpre [Tk, 2N] = sigma'(Hpre) * row_scale * acc instead of dH, and per row and 128-column slab the
+  // partial dot <acc, silu(gate) * up> whose sum over the slabs is Alg. 2's dp for that row.
+  const void *Hpre_in = nullptr;
+  const float *row_scale = nullptr;
+  float *dp_part = nullptr;
 };
 struct DWArgs {       // dW[e] = sum_{i in segment e} A[i, :]^T B[i, :]   (both operands expert-sorted)
   const void *A;      // [Tk, M]
@@ -119,6 +135,7 @@ int init_stream_kernels();
 constexpr size_t S2S_TAIL_WS_BYTES = (size_t)256 * 256 * 256 * sizeof(float);   // 256 partial tiles of 256 x 256 fp32
 bool s2s_stream_supported(const S2SArgs &a);
 bool s2s_stream_swiglu_supported(const S2SArgs &a);
+bool s2s_stream_swiglu_bwd_supported(const S2SArgs &a);
 int launch_s2s_stream(hipStream_t s, const S2SArgs &a);
 // Small-batch (decoding) forward products: 32-row tiles, one wavefront each, bound by the weight stream.
 // Takes a.H like the persistent kernel (fused SwiGLU).

@@ -135,6 +135,75 @@ __device__ __forceinline__ void store_wave_tile_swiglu(const f32x16 (&acc)[FR][F
   }
 }
 
+// Epilogue of the second ParallelLinear's input-gradient product with the SwiGLU derivative and Alg. 2's dp folded in.
+// The accumulators hold dH / p for 128 hidden units of 128 expert-sorted rows (the product ran on the unweighted
+// upstream rows).  Per 32-row fragment row the lane fetches the matching gate and up pre-activations (its own row,
+// its own 4-column groups: 8-byte loads), forms h = silu(gate) * up and the partial dot <acc, h> (summed over the
+// wavefront's 128 columns: one slab of dp), scales the accumulators by the row's routing weight and writes
+//   dgate = dh * up * (sig + silu * (1 - sig)),  dup = dh * silu
+// to the two halves of dHpre through the 32 x 64 LDS patch.  Rows past the segment read its last row and columns
+// past the width read column 0; neither is stored or added to the dot.
+template <typename RowFn>
+__device__ __forceinline__ void store_wave_tile_swiglu_bwd(const f32x16 (&acc)[FR][FR], char *patch, RowFn dst_row,
+                                                           const bf16_t *Hpre, bf16_t *dHpre, const float *row_scale,
+                                                           float *dp_part, int part_ld, int part_col, int half_n, int gcol,
+                                                           int row_base, int row_end, int lane) {
+  __asm__ volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  const size_t ld = (size_t)2 * half_n;
+#pragma unroll
+  for (int fm = 0; fm < FR; ++fm) {
+    const int grow = row_base + fm * 32 + (lane & 31);
+    const bool live = grow < row_end;
+    const int srow = live ? grow : row_end - 1;
+    const bf16_t *src = Hpre + (size_t)srow * ld;
+    const float scale = row_scale[srow];
+    float dp = 0.f;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      sched_fence();
+      bf16x4 gt[2][4], up[2][4];
+#pragma unroll
+      for (int f2 = 0; f2 < 2; ++f2)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int col = gcol + half * 64 + f2 * 32 + 8 * g + 4 * (lane >> 5);
+          const int cc = col < half_n ? col : 0;
+          gt[f2][g] = *reinterpret_cast<const bf16x4 *>(src + cc);
+          up[f2][g] = *reinterpret_cast<const bf16x4 *>(src + half_n + cc);
+        }
+      bf16x4 du[2][4];
+#pragma unroll
+      for (int f2 = 0; f2 < 2; ++f2)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int col = gcol + half * 64 + f2 * 32 + 8 * g + 4 * (lane >> 5);
+          bf16x4 dg;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const float a = acc_read(acc[fm][half * 2 + f2][g * 4 + q]);
+            const float gate = (float)gt[f2][g][q], u = (float)up[f2][g][q];
+            const float sig = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gate));
+            const float silu = gate * sig;
+            if (col < half_n) dp = fmaf(a, silu * u, dp);
+            const float dh = scale * a;
+            dg[q] = (bf16_t)(dh * u * (sig + silu * (1.0f - sig)));
+            du[f2][g][q] = (bf16_t)(dh * silu);
+          }
+          *reinterpret_cast<bf16x4 *>(patch + (lane & 31) * EPI_ROW_BYTES + (f2 * 32 + 8 * g + 4 * (lane >> 5)) * 2) = dg;
+        }
+      flush_patch(patch, dst_row, fm, dHpre, ld, 0, gcol + half * 64, half_n, lane);
+#pragma unroll
+      for (int f2 = 0; f2 < 2; ++f2)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<bf16x4 *>(patch + (lane & 31) * EPI_ROW_BYTES + (f2 * 32 + 8 * g + 4 * (lane >> 5)) * 2) = du[f2][g];
+      flush_patch(patch, dst_row, fm, dHpre, ld, half_n, gcol + half * 64, half_n, lane);
+    }
+    dp += __shfl_xor(dp, 32, 64);
+    if (live && lane < 32) dp_part[(size_t)grow * part_ld + part_col] = dp;
+  }
+}
+
 // A wavefront's 128 x 128 accumulators as fp32 into a 256-wide partial tile (chunks of a split contraction).
 __device__ __forceinline__ void store_wave_partial(const f32x16 (&acc)[FR][FR], float *dst, int lane) {
   __asm__ volatile("s_nop 15\n\ts_nop 15" ::: "memory");
@@ -296,13 +365,16 @@ template <bool TRANS_W> struct S2SStreamOps {
   }
 };
 
-// ACT 1: fused SwiGLU keeping the pre-activation, 2: without.  STATIC4: the contraction is a multiple of four
+// ACT 1: fused SwiGLU keeping the pre-activation, 2: without, 3: fused SwiGLU derivative and dp (the W2^T input-gradient
+// product of Alg. 3's backward, see store_wave_tile_swiglu_bwd).  STATIC4: the contraction is a multiple of four
 // half-steps, so every tile starts in LDS stage 0 and the loop is written out four slots at a time with the
 // stage as a compile-time constant: all LDS addresses become a loop-invariant register plus an immediate.
 template <bool TRANS_W, bool SCATTER_OUT, int ACT = 0, bool STATIC4 = false>
 __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int tiles_n, int group_m, uint32_t magic_a) {
-  static_assert(ACT == 0 || (!TRANS_W && !SCATTER_OUT), "the fused activation belongs to the forward, sorted-output product");
-  constexpr bool SWIGLU = ACT != 0;
+  constexpr bool SWIGLU = ACT == 1 || ACT == 2;
+  constexpr bool SWIGLU_BWD = ACT == 3;
+  static_assert(!SWIGLU || (!TRANS_W && !SCATTER_OUT), "the fused activation belongs to the forward, sorted-output product");
+  static_assert(!SWIGLU_BWD || (TRANS_W && !SCATTER_OUT), "the fused derivative belongs to the W^T product with sorted rows in and out");
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   __shared__ int s_off[MAX_E + 1];
   // Order indices of the rows of up to four open tiles.  With the shortest contraction the kernel takes (three
@@ -510,6 +582,9 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
     };
     if (SWIGLU)
       store_wave_tile_swiglu<ACT == 1>(acc, patch, dst_row, (bf16_t *)a.C, (bf16_t *)a.H, a.N / 2, ct.n0 + wn * (TB / 4), lane);
+    else if (SWIGLU_BWD)
+      store_wave_tile_swiglu_bwd(acc, patch, dst_row, (const bf16_t *)a.Hpre_in, (bf16_t *)a.C, a.row_scale, a.dp_part, 2 * tiles_n,
+                                 (ct.n0 / TB) * 2 + wn, a.N, ct.n0 + wn * (TB / 2), rbase, ct.row_end, lane);
     else if (ct.part >= 0)
       store_wave_partial(acc, a.tail_ws + (size_t)ct.part * TB * TB + (size_t)(wm * (TB / 2)) * TB + wn * (TB / 2), lane);
     else
@@ -799,7 +874,7 @@ template <bool TRANS_W, bool SCATTER_OUT, int ACT = 0> int launch_s2s_stream_cfg
                              : launch_s2s_stream_one<TRANS_W, SCATTER_OUT, ACT, false>(s, a);
 }
 template <bool TRANS_W, bool SCATTER_OUT, int ACT, bool STATIC4> int launch_s2s_stream_one(hipStream_t s, const S2SArgs &a) {
-  int tiles_n = ACT ? ceil_div(a.N / 2, TB / 2) : ceil_div(a.N, TB);
+  int tiles_n = (ACT == 1 || ACT == 2) ? ceil_div(a.N / 2, TB / 2) : ceil_div(a.N, TB);
   long long tiles_m = ceil_div(a.Tk, TB) + a.E;     // upper bound on sum_e ceil(n_e / 256)
   int group_m = 4;
   if (tiles_m * tiles_n > 0x7fffffffLL) return SMOE_ERR_UNSUPPORTED;
@@ -852,12 +927,21 @@ bool s2s_stream_supported(const S2SArgs &a) {
          (w_rows + HK) * a.ldw * 2 < 0x100000000LL;
 }
 
+bool s2s_stream_swiglu_bwd_supported(const S2SArgs &a) {
+  return s2s_stream_supported(a) && a.trans_w && !a.c_map.o && !a.a_map.o && a.Hpre_in && a.row_scale && a.dp_part &&
+         a.N % 8 == 0;
+}
+
 bool s2s_stream_swiglu_supported(const S2SArgs &a) {
   return s2s_stream_supported(a) && !a.trans_w && !a.c_map.o && a.H && a.N % 16 == 0;
 }
 
 int launch_s2s_stream(hipStream_t s, const S2SArgs &a) {
   const bool scatter_out = a.c_map.o != nullptr;
+  if (a.dp_part) {
+    if (!s2s_stream_swiglu_bwd_supported(a)) return SMOE_ERR_UNSUPPORTED;
+    return launch_s2s_stream_cfg<true, false, 3>(s, a);
+  }
   if (a.H) {
     if (!s2s_stream_swiglu_supported(a)) return SMOE_ERR_UNSUPPORTED;
     return a.C ? launch_s2s_stream_cfg<false, false, 1>(s, a) : launch_s2s_stream_cfg<false, false, 2>(s, a);
@@ -885,6 +969,7 @@ int init_stream_kernels() {
   if (rc == SMOE_OK) rc = init_s2s_pair<true, true, 0>();
   if (rc == SMOE_OK) rc = init_s2s_pair<false, false, 1>();
   if (rc == SMOE_OK) rc = init_s2s_pair<false, false, 2>();
+  if (rc == SMOE_OK) rc = init_s2s_pair<true, false, 3>();
   if (rc == SMOE_OK) rc = set_lds_limit(dw_stream_kernel, STREAM_LDS_BYTES);
   return rc;
 }

@@ -170,3 +170,49 @@ def test_fused_swiglu_forward_every_row_over_several_rounds(smoe, d_model, d_exp
     Yref = np.stack([oracle.mlp_token_fwd(X64[t], ei[t], g64[t], W164, W264, cfg.act)[0] for t in toks])
     assert_close(Y[torch.from_numpy(toks).cuda()], Yref, torch.bfloat16, "Y (sampled tokens)")
     assert bool(torch.isfinite(Y.float()).all())
+
+
+def test_fused_swiglu_backward_over_several_rounds(smoe):
+    """The W2^T input-gradient product with the activation's derivative and the routing-weight gradient in its
+    epilogue, 500+ tiles.  dHpre itself is scratch; what it feeds is compared: dgates and dX on tokens drawn from
+    every tile of every expert, two columns pairs of dW1 and two rows of dW2 from every 256-unit tile for every
+    expert (each sums over all the expert's rows), and every output must be free of the poison the workspace
+    and outputs start with.  The forward's unweighted second product is not kept for such shapes."""
+    cfg = si.custom("fused-bwd-rounds", T=4096, d_model=128, d_expert=4096, E=8, k=2, act=si.ACT_SWIGLU, dtype="bf16",
+                    zipf_s=1.2)
+    case = si.mlp_case(cfg, 23)
+    ei, g, se, o, off = oracle_routing(case["logits"], cfg.k, cfg.E)
+    gi, gg = smoe.topk_gate(case["logits"].cuda(), cfg.k)
+    r = smoe.route(gi, cfg.E)
+    assert np.array_equal(r.sorted_scattered_idxs.cpu().numpy(), o)
+    tiles = _m_tiles(off) * (cfg.d_expert // TB)
+    _log(f"input-gradient tiles {tiles}")
+    assert tiles >= 2 * GRID
+    X, W1, W2, dY = (case[n].cuda() for n in ("X", "W1", "W2", "dY"))
+    Y, buf = smoe.mlp_fwd(X, W1, W2, r, cfg.k, gg, cfg.act)
+    assert buf.Yhat is None
+    dX, dW1, dW2, dg = smoe.mlp_bwd(dY, X, W1, W2, r, cfg.k, gg, cfg.act, buf)
+    torch.cuda.synchronize()
+    for name, t in (("dX", dX), ("dW1", dW1), ("dW2", dW2), ("dgates", dg), ("Y", Y)):
+        assert bool(torch.isfinite(t.float()).all()), f"{name} holds entries no kernel wrote"
+    g64 = oracle_gates_f32(g)
+    X64, W164, W264, dY64 = (si.as_f64(case[n]) for n in ("X", "W1", "W2", "dY"))
+    rng = np.random.default_rng(9)
+    rows = np.concatenate([rng.choice(np.arange(a, min(a + TB, int(off[e + 1]))), size=min(6, int(off[e + 1]) - a), replace=False)
+                           for e in range(cfg.E) for a in range(int(off[e]), int(off[e + 1]), TB)])
+    toks = np.unique(o[rows] // cfg.k)
+    _log(f"{len(toks)} tokens from {len(rows)} sampled rows")
+    ref = [oracle.mlp_token_bwd(X64[t], dY64[t], ei[t], g64[t], W164, W264, cfg.act) for t in toks]
+    tt = torch.from_numpy(toks).cuda()
+    assert_close(dX[tt], np.stack([q[0] for q in ref]), torch.bfloat16, "dX (tokens from every tile)")
+    assert_close(dg[tt], np.stack([q[1] for q in ref]), torch.bfloat16, "dgates (tokens from every tile)")
+    units = _per_tile_columns(cfg.d_expert, 2, rng)
+    ut = torch.from_numpy(units).cuda()
+    r1, g1, r2, g2 = [], [], [], []
+    for e in range(cfg.E):
+        r1.append(oracle.mlp_dW1_cols(dY64, X64, W164, W264, ei, g64, cfg.act, e, units))
+        g1.append(torch.stack([dW1[e][:, ut].T, dW1[e][:, ut + cfg.d_expert].T], 1).float().cpu().numpy())
+        r2.append(oracle.mlp_dW2_rows(dY64, X64, W164, W264, ei, g64, cfg.act, e, units))
+        g2.append(dW2[e][ut].float().cpu().numpy())
+    assert_close(np.stack(g1), np.stack(r1), torch.bfloat16, "dW1 (two unit pairs per tile)")
+    assert_close(np.stack(g2), np.stack(r2), torch.bfloat16, "dW2 (two rows per tile)")

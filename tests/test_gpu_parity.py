@@ -227,7 +227,8 @@ def _mlp_parity(smoe, cfg, seed, plain=False, mode=None):
     errs["Y"] = assert_close(Y, ref["Y"], td, "Y")
     errs["Hpre"] = assert_close(buf.Hpre, ref["Hpre"][o], td, "Hpre (grouped)")
     errs["H"] = assert_close(buf.H, ref["H"][o], td, "H (grouped)")
-    errs["Yhat"] = assert_close(buf.Yhat, ref["Yhat"], td, "Yhat (scattered)")
+    if buf.Yhat is not None:         # not kept when the backward pass of this shape forms dp in a product's epilogue
+        errs["Yhat"] = assert_close(buf.Yhat, ref["Yhat"], td, "Yhat (scattered)")
     gref = oracle.mlp_bwd(dY64, X64, W164, W264, ei, g64, cfg.act)
     errs["dX"] = assert_close(dX, gref["dX"], td, "dX")
     errs["dW1"] = assert_close(dW1, gref["dW1"], td, "dW1")
