@@ -411,6 +411,25 @@ def main():
     s2s_flops = 2.0 * cfg.Tk * cfg.d_model * d_h
     achieved = s2s_flops / (ms_s2s * 1e-3) / 1e12
 
+    # Clock the compute units ran at during one more launch of that kernel (the persistent kernels can report the
+    # shader-clock cycles and the 100 MHz real-time ticks each block saw: smoe_set_clock_probe).
+    clock = None
+    if cfg.dtype == "bf16" and not decode:
+        probe = torch.zeros(512, dtype=torch.int64, device=dev)
+        smoe.set_clock_probe(probe)
+        try:
+            s2s_once()
+            torch.cuda.synchronize()
+        finally:
+            smoe.set_clock_probe(None)
+        pr = probe.cpu().numpy().reshape(256, 2).astype(np.float64)
+        ok = pr[:, 1] > 0
+        if ok.any():
+            mhz = np.where(ok, pr[:, 0] / np.maximum(pr[:, 1], 1) * 100.0, np.nan)
+            clock = {"mean": float(np.nanmean(mhz)), "min": float(np.nanmin(mhz)), "max": float(np.nanmax(mhz)),
+                     "per_xcd": [float(np.nanmean(mhz[x::8])) for x in range(8)],
+                     "block_us_min": float(pr[ok, 1].min() / 100.0), "block_us_max": float(pr[ok, 1].max() / 100.0)}
+
     if args.calibrate_copy:   # known traffic: reads 1 GiB, writes 1 GiB per launch
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -442,6 +461,9 @@ def main():
     roofline, other = (by_hbm, by_mfma) if t_hbm > t_mfma else (by_mfma, by_hbm)
     roofline["min_ms_mfma"], roofline["min_ms_hbm"] = t_mfma * 1e3, t_hbm * 1e3
     roofline["other_roofline"] = {k_: other[k_] for k_ in ("bound", "achieved", "peak", "unit", "frac")}
+    if clock:      # the published peak assumes 2.4 GHz; this is the clock the kernel actually got
+        roofline["shader_clock_mhz"] = clock
+        roofline["frac_of_peak_at_measured_clock"] = achieved / (peak * clock["mean"] / 2400.0)
 
     # Whole forward pass against HBM: algorithmic bytes with the activation counted as its own pass (each used expert's
     # W1 and W2 once, gathered X rows, Hpre written and read, H written and read, Yhat written and read, Y written).

@@ -87,6 +87,14 @@ int smoe_abi_version(void);
  * context may be in progress. */
 int smoe_set_kernel_mode(smoe_ctx *ctx, int mode);
 
+/* Measurement aid.  With a device array of 512 uint64 set, every launch of the persistent scatter2scatter
+ * kernels (the products of smoe_plinear_fwd / _bwd, smoe_plinear_act_fwd, smoe_mlp_fwd / _bwd) makes block b
+ * store, when it ends, the shader-clock cycles and the ticks of the constant 100 MHz counter between its first
+ * and last instruction in entries 2b and 2b+1: cycles / ticks * 100 is the clock in MHz the compute unit ran at
+ * (blocks b, b+8, ... share an XCD).  Later launches overwrite the array.  NULL (the default) turns it off.
+ * Host-only; writes the context, so no other call on it may be in progress. */
+int smoe_set_clock_probe(smoe_ctx *ctx, uint64_t *device_array);
+
 /* ---- routing: Sec. 3.1 step 1 -------------------------------------------------------
  * For each token keeps the k largest of its E router logits (ties to the lower expert
  * id, slots ordered by descending logit) and the softmax over those k logits.

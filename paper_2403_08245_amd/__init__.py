@@ -20,7 +20,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libsmoe.so")
 
 EXPORTS = [
-    "smoe_create", "smoe_destroy", "smoe_strerror", "smoe_abi_version", "smoe_set_kernel_mode",
+    "smoe_create", "smoe_destroy", "smoe_strerror", "smoe_abi_version", "smoe_set_kernel_mode", "smoe_set_clock_probe",
     "smoe_topk_gate", "smoe_topk_gate_bwd", "smoe_route_workspace_bytes", "smoe_route", "smoe_route_noalloc",
     "smoe_plinear_fwd", "smoe_plinear_bwd_workspace_bytes", "smoe_plinear_bwd",
     "smoe_plinear_act_fwd_workspace_bytes", "smoe_plinear_act_fwd", "smoe_mlp_fwd_workspace_bytes", "smoe_mlp_fwd", "smoe_mlp_saves_yhat", "smoe_mlp_bwd_workspace_bytes", "smoe_mlp_bwd",
@@ -54,6 +54,7 @@ lib.smoe_destroy.restype = None
 lib.smoe_strerror.argtypes = [_i]
 lib.smoe_strerror.restype = ctypes.c_char_p
 lib.smoe_set_kernel_mode.argtypes = [_vp, _i]
+lib.smoe_set_clock_probe.argtypes = [_vp, _vp]
 lib.smoe_topk_gate.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp, _vp]
 lib.smoe_topk_gate_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp]
 lib.smoe_attention_fwd.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp]
@@ -115,6 +116,14 @@ def ctx(device: int | None = None) -> ctypes.c_void_p:
 
 def set_kernel_mode(mode: int):
     _check(lib.smoe_set_kernel_mode(ctx(), mode), "smoe_set_kernel_mode")
+
+
+def set_clock_probe(buf: torch.Tensor | None):
+    """Device int64 tensor of 512 entries that the persistent scatter2scatter kernels report their clocks to
+    (see smoe_set_clock_probe), or None to turn the probe off."""
+    if buf is not None and (buf.dtype != torch.int64 or buf.numel() < 512 or not buf.is_cuda):
+        raise ValueError("need a device int64 tensor of 512 entries")
+    _check(lib.smoe_set_clock_probe(ctx(), _p(buf)), "smoe_set_clock_probe")
 
 
 def _stream() -> int:

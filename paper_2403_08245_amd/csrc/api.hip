@@ -17,6 +17,7 @@ bool dtype_ok(int dt) { return dt == SMOE_F32 || dt == SMOE_BF16; }
 
 int run_s2s(smoe_ctx *ctx, hipStream_t s, smoe_dtype dt, S2SArgs a) {
   a.grid = ctx->stream_grid;
+  a.clock_probe = ctx->clock_probe;
   if (dt == SMOE_BF16 && ctx->kernel_mode == 0 && s2s_decode_supported(a)) return launch_s2s_decode(s, a);
   if (dt == SMOE_BF16 && ctx->kernel_mode == 0 && s2s_stream_supported(a)) return launch_s2s_stream(s, a);
   if (dt == SMOE_BF16 && ctx->kernel_mode != 1 && s2s_mfma_supported(a)) return launch_s2s_mfma(s, a);
@@ -79,6 +80,7 @@ int smoe_create(smoe_ctx **out, int device) {
   // persistent kernels: one block per compute unit, dealt to the XCDs in eight equal shares
   c->stream_grid = c->num_cu >= 256 ? 256 : (c->num_cu & ~7);
   c->kernel_mode = 0;
+  c->clock_probe = nullptr;
   c->route_scratch = nullptr;
   // kernel attributes and the address of a __device__ array are per device: set them with this context's device current, then restore the caller's
   int prev = -1;
@@ -102,6 +104,12 @@ void smoe_destroy(smoe_ctx *ctx) { delete ctx; }
 int smoe_set_kernel_mode(smoe_ctx *ctx, int mode) {
   if (!ctx || mode < 0 || mode > 2) return SMOE_ERR_INVALID_ARG;
   ctx->kernel_mode = mode;
+  return SMOE_OK;
+}
+
+int smoe_set_clock_probe(smoe_ctx *ctx, uint64_t *device_array) {
+  if (!ctx) return SMOE_ERR_INVALID_ARG;
+  ctx->clock_probe = (unsigned long long *)device_array;
   return SMOE_OK;
 }
 
@@ -325,6 +333,7 @@ static int hidden_forward(smoe_ctx *ctx, hipStream_t s, smoe_dtype dtype, smoe_a
   S2SArgs fused = a1;
   fused.H = H;
   fused.grid = ctx->stream_grid;
+  fused.clock_probe = ctx->clock_probe;
   if (act == SMOE_ACT_SWIGLU && dtype == SMOE_BF16 && ctx->kernel_mode == 0 &&
       (s2s_decode_supported(fused) || s2s_stream_swiglu_supported(fused))) {
     // SwiGLU in the product's epilogue: H comes straight from the fp32 accumulators, and the
@@ -509,6 +518,7 @@ int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
     x2.row_scale = gsorted;
     x2.dp_part = dp_part;
     x2.grid = ctx->stream_grid;
+    x2.clock_probe = ctx->clock_probe;
     rc = launch_s2s_stream(s, x2);
     if (rc != SMOE_OK) return rc;
     rc = launch_dp_reduce(s, dp_part, L.part_ld, r->sorted_scattered_idxs, dgates, Tk);

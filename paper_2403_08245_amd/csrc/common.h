@@ -11,6 +11,7 @@ struct smoe_ctx {
   int device;
   int num_cu;
   int stream_grid;  // blocks of the persistent kernels: one per compute unit, a multiple of 8 (one share per XCD), at most 256
+  unsigned long long *clock_probe;  // device array the persistent s2s kernels report their clocks to, or NULL (smoe_set_clock_probe)
   int kernel_mode;  // 0 auto, 1 plain tiled kernels only, 2 one block per tile (testing aid, see smoe_set_kernel_mode)
   int32_t *route_scratch;  // this device's copy of the routing kernels' static scratch array (smoe_route_noalloc)
 };
@@ -105,6 +106,9 @@ struct S2SArgs {      // C[out(i), :] = A[in(i), :] * op(W[e(i)])   for sorted r
   // weight of every sorted row) and dp_part [Tk, 2 * ceil(N / 256)] fp32 set, the epilogue writes
   // C = dHpre [Tk, 2N] = sigma'(Hpre) * row_scale * acc instead of dH, and per row and 128-column slab the
   // partial dot <acc, silu(gate) * up> whose sum over the slabs is Alg. 2's dp for that row.
+  // Optional [2 * grid] device array: block b leaves the shader-clock cycles and the 100 MHz real-time ticks between its
+  // first and last instruction in entries 2b and 2b+1 (measurement aid: the ratio is the clock the block ran at).
+  unsigned long long *clock_probe = nullptr;
   const void *Hpre_in = nullptr;
   const float *row_scale = nullptr;
   float *dp_part = nullptr;

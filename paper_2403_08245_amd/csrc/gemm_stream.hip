@@ -391,6 +391,7 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
   const int32_t *o = a.a_map.o ? a.a_map.o : a.c_map.o;   // both maps use the same order indices
   const bf16_t *A = (const bf16_t *)a.A;
 
+  const unsigned long long probe_c0 = a.clock_probe ? clock64() : 0ull, probe_t0 = a.clock_probe ? wall_clock64() : 0ull;
   for (int i = threadIdx.x; i <= a.E; i += NTHREADS) s_off[i] = a.offsets[i];
   __syncthreads();
 
@@ -592,6 +593,10 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
     if (!next_tile(ct)) break;
   }
   wait_loads<0>();
+  if (a.clock_probe && threadIdx.x == 0) {
+    a.clock_probe[2 * blockIdx.x] = clock64() - probe_c0;
+    a.clock_probe[2 * blockIdx.x + 1] = wall_clock64() - probe_t0;
+  }
 }
 
 // Second pass of a split last round: adds the chunks' fp32 partial tiles in chunk order, rounds once and
