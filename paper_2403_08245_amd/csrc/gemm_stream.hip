@@ -38,111 +38,169 @@ __device__ __forceinline__ float acc_read(float a) {
   return v;
 }
 
+// ---- the LDS patch as a pipeline ------------------------------------------------------------------------
+// A 32 x 64 block of bf16 results goes accumulator layout -> patch (8-byte writes, a lane's 4 consecutive columns)
+// -> whole rows back out (16-byte reads, eight lanes per 128-byte row) -> global memory.  LDS operations of one
+// wavefront execute in order, so the block's row reads may be issued right behind its writes and the next block's
+// writes right behind those reads, with no wait in between; only the global stores need the read data.  The
+// stores of block n are therefore issued after block n+1 has been written and read: the LDS latency of one block
+// hides behind the accumulator reads and conversions of the next one instead of being sat out four times per block.
+struct PatchRows {
+  bf16x8 v[4];
+};
+__device__ __forceinline__ PatchRows read_patch_rows(const char *patch, int lane) {
+  PatchRows r;
+#pragma unroll
+  for (int it = 0; it < 4; ++it)
+    r.v[it] = *reinterpret_cast<const bf16x8 *>(patch + (it * 8 + (lane >> 3)) * EPI_ROW_BYTES + (lane & 7) * 16);
+  return r;
+}
+// The rows read from the patch and where they go: destination rows of the lane's four chunks (-1: none), the
+// tensor, its row stride, the lane's column in it, and whether that column exists.
+struct RowStore {
+  PatchRows rows;
+  int drow[4];
+  bf16_t *base;
+  size_t ld;
+  int col;
+  bool col_ok, have;
+};
+__device__ __forceinline__ void issue_row_store(const RowStore &p, int lane) {
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    bf16_t *dst = (p.drow[it] >= 0 && p.col_ok) ? p.base + (size_t)p.drow[it] * p.ld + p.col : (bf16_t *)g_trash + lane * 8;
+    // Non-temporal: a launch streams gigabytes of output through each XCD's 4 MB L2, which also holds the operand
+    // panels its 32 compute units share; marking the lines for early eviction keeps them from pushing the panels out
+    // (3 % on the first product of the Mixtral-shaped layer, neutral on products with narrow outputs).
+    __builtin_nontemporal_store(p.rows.v[it], reinterpret_cast<bf16x8 *>(dst));   // masked lanes hit the landing zone
+  }
+}
+// One block through the pipeline: write_block() fills the patch from the accumulators; the previous block's
+// stores go out behind this block's LDS traffic.  gcol is the block's first column among the `limit` columns of
+// its destination, col0 the offset of those columns inside a row of `base`.
+template <typename WriteFn>
+__device__ __forceinline__ void pipe_block(RowStore &pend, const char *patch, int lane, WriteFn write_block, const int (&drow)[4],
+                                           bf16_t *base, size_t ld, int col0, int gcol, int limit) {
+  sched_fence();
+  write_block();
+  RowStore cur;
+  cur.rows = read_patch_rows(patch, lane);
+  sched_fence();
+  if (pend.have) issue_row_store(pend, lane);
+#pragma unroll
+  for (int it = 0; it < 4; ++it) cur.drow[it] = drow[it];
+  cur.base = base;
+  cur.ld = ld;
+  cur.col = col0 + gcol + (lane & 7) * 8;
+  cur.col_ok = gcol + (lane & 7) * 8 < limit;
+  cur.have = true;
+  pend = cur;
+}
+// destination rows of the lane's chunks in every 32-row fragment row of the wave tile
+template <typename RowFn> __device__ __forceinline__ void chunk_rows(RowFn dst_row, int lane, int (&drow)[FR][4]) {
+#pragma unroll
+  for (int fm = 0; fm < FR; ++fm)
+#pragma unroll
+    for (int it = 0; it < 4; ++it) drow[fm][it] = dst_row(fm * 32 + it * 8 + (lane >> 3));
+}
+// accumulators of one 32 x 32 fragment pair (64 columns) -> patch, rounded to bf16
+__device__ __forceinline__ void acc_block_to_patch(const f32x16 &a0, const f32x16 &a1, char *patch, int lane) {
+#pragma unroll
+  for (int f2 = 0; f2 < 2; ++f2)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      bf16x4 v;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) v[q] = (bf16_t)acc_read(f2 == 0 ? a0[g * 4 + q] : a1[g * 4 + q]);
+      *reinterpret_cast<bf16x4 *>(patch + (lane & 31) * EPI_ROW_BYTES + (f2 * 32 + 8 * g + 4 * (lane >> 5)) * 2) = v;
+    }
+}
+
 template <typename RowFn>
 __device__ __forceinline__ void store_wave_tile(const f32x16 (&acc)[FR][FR], char *patch, RowFn dst_row, bf16_t *C,
                                                 int ldc, int wcol, int ncols, int lane) {
   // the last matrix instructions must have retired before their results are read by hand
   __asm__ volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  int drow[FR][4];
+  chunk_rows(dst_row, lane, drow);
+  RowStore pend;
+  pend.have = false;
 #pragma unroll
-  for (int fm = 0; fm < FR; ++fm) {
+  for (int fm = 0; fm < FR; ++fm)
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      sched_fence();   // one pass at a time: keeps the accumulator reads from piling up in registers
-#pragma unroll
-      for (int f2 = 0; f2 < 2; ++f2) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          bf16x4 v;
-#pragma unroll
-          for (int q = 0; q < 4; ++q) v[q] = (bf16_t)acc_read(acc[fm][half * 2 + f2][g * 4 + q]);
-          int col = f2 * 32 + 8 * g + 4 * (lane >> 5);
-          *reinterpret_cast<bf16x4 *>(patch + (lane & 31) * EPI_ROW_BYTES + col * 2) = v;
-        }
-      }
-#pragma unroll
-      for (int it = 0; it < 4; ++it) {
-        int r = it * 8 + (lane >> 3);
-        int chunk = lane & 7;
-        bf16x8 v = *reinterpret_cast<const bf16x8 *>(patch + r * EPI_ROW_BYTES + chunk * 16);
-        int dst = dst_row(fm * 32 + r);
-        int col = wcol + half * 64 + chunk * 8;
-        bf16_t *p = (dst >= 0 && col < ncols) ? C + (size_t)dst * ldc + col : (bf16_t *)g_trash + lane * 8;
-        *reinterpret_cast<bf16x8 *>(p) = v;   // straight-line code: masked lanes hit the landing zone
-      }
-    }
-  }
+    for (int half = 0; half < 2; ++half)
+      pipe_block(pend, patch, lane, [&] { acc_block_to_patch(acc[fm][half * 2], acc[fm][half * 2 + 1], patch, lane); }, drow[fm], C,
+                 (size_t)ldc, 0, wcol + half * 64, ncols);
+  sched_fence();
+  issue_row_store(pend, lane);
 }
 
 // Epilogue of a SwiGLU tile: the wavefront's 128 accumulator columns are 64 gate columns (fragments 0, 1)
 // and the 64 up columns that pair with them (fragments 2, 3), so a lane holds both factors of each hidden
 // unit in matching registers.  Writes the pre-activation halves (KEEP) and H = silu(gate) * up, each
-// through the same 32 x 64 LDS patch as above and as straight-line code.  gcol is the first gate column
-// of this wavefront, half_n the number of gate columns of the layer.
-template <typename RowFn>
-__device__ __forceinline__ void flush_patch(const char *patch, RowFn dst_row, int fm, bf16_t *dst_base, size_t ld, int col0,
-                                            int gcol, int half_n, int lane) {
-#pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    int r = it * 8 + (lane >> 3);
-    int chunk = lane & 7;
-    bf16x8 v = *reinterpret_cast<const bf16x8 *>(patch + r * EPI_ROW_BYTES + chunk * 16);
-    int dst = dst_row(fm * 32 + r);
-    int col = gcol + chunk * 8;
-    bf16_t *p = (dst >= 0 && col < half_n) ? dst_base + (size_t)dst * ld + col0 + col : (bf16_t *)g_trash + lane * 8;
-    *reinterpret_cast<bf16x8 *>(p) = v;
-  }
-}
-
+// through the same pipeline as above.  gcol is the first gate column of this wavefront, half_n the number of
+// gate columns of the layer.
 template <bool KEEP, typename RowFn>
 __device__ __forceinline__ void store_wave_tile_swiglu(const f32x16 (&acc)[FR][FR], char *patch, RowFn dst_row, bf16_t *C,
                                                        bf16_t *H, int half_n, int gcol, int lane) {
   __asm__ volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  int drow[FR][4];
+  chunk_rows(dst_row, lane, drow);
+  RowStore pend;
+  pend.have = false;
 #pragma unroll
   for (int fm = 0; fm < FR; ++fm) {
     if (KEEP) {
 #pragma unroll
-      for (int half = 0; half < 2; ++half) {   // gate columns, then up columns of the pre-activation
-        sched_fence();
-#pragma unroll
-        for (int f2 = 0; f2 < 2; ++f2)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            bf16x4 v;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) v[q] = (bf16_t)acc_read(acc[fm][half * 2 + f2][g * 4 + q]);
-            int col = f2 * 32 + 8 * g + 4 * (lane >> 5);
-            *reinterpret_cast<bf16x4 *>(patch + (lane & 31) * EPI_ROW_BYTES + col * 2) = v;
-          }
-        flush_patch(patch, dst_row, fm, C, (size_t)2 * half_n, half * half_n, gcol, half_n, lane);
-      }
+      for (int half = 0; half < 2; ++half)   // gate columns, then up columns of the pre-activation
+        pipe_block(pend, patch, lane, [&] { acc_block_to_patch(acc[fm][half * 2], acc[fm][half * 2 + 1], patch, lane); }, drow[fm],
+                   C, (size_t)2 * half_n, half * half_n, gcol, half_n);
     }
-    sched_fence();
+    pipe_block(pend, patch, lane, [&] {
 #pragma unroll
-    for (int f2 = 0; f2 < 2; ++f2)
+      for (int f2 = 0; f2 < 2; ++f2)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        bf16x4 v;
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 v;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          float gate = acc_read(acc[fm][f2][g * 4 + q]), up = acc_read(acc[fm][2 + f2][g * 4 + q]);
-          float sig = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gate));
-          v[q] = (bf16_t)(gate * sig * up);
+          for (int q = 0; q < 4; ++q) {
+            float gate = acc_read(acc[fm][f2][g * 4 + q]), up = acc_read(acc[fm][2 + f2][g * 4 + q]);
+            float sig = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gate));
+            v[q] = (bf16_t)(gate * sig * up);
+          }
+          *reinterpret_cast<bf16x4 *>(patch + (lane & 31) * EPI_ROW_BYTES + (f2 * 32 + 8 * g + 4 * (lane >> 5)) * 2) = v;
         }
-        int col = f2 * 32 + 8 * g + 4 * (lane >> 5);
-        *reinterpret_cast<bf16x4 *>(patch + (lane & 31) * EPI_ROW_BYTES + col * 2) = v;
-      }
-    flush_patch(patch, dst_row, fm, H, (size_t)half_n, 0, gcol, half_n, lane);
+    }, drow[fm], H, (size_t)half_n, 0, gcol, half_n);
   }
+  sched_fence();
+  issue_row_store(pend, lane);
 }
 
 // Epilogue of the second ParallelLinear's input-gradient product with the SwiGLU derivative and Alg. 2's dp folded in.
 // The accumulators hold dH / p for 128 hidden units of 128 expert-sorted rows (the product ran on the unweighted
 // upstream rows).  Per 32-row fragment row the lane fetches the matching gate and up pre-activations (its own row,
-// its own 4-column groups: 8-byte loads), forms h = silu(gate) * up and the partial dot <acc, h> (summed over the
-// wavefront's 128 columns: one slab of dp), scales the accumulators by the row's routing weight and writes
+// its own 4-column groups: 8-byte loads, the next 64 columns requested before the current ones are used), forms
+// h = silu(gate) * up and the partial dot <acc, h> (summed over the wavefront's 128 columns: one slab of dp), scales
+// the accumulators by the row's routing weight and writes
 //   dgate = dh * up * (sig + silu * (1 - sig)),  dup = dh * silu
-// to the two halves of dHpre through the 32 x 64 LDS patch.  Rows past the segment read its last row and columns
+// to the two halves of dHpre through the patch pipeline.  Rows past the segment read its last row and columns
 // past the width read column 0; neither is stored or added to the dot.
+struct GateUp {
+  bf16x4 gt[2][4], up[2][4];
+};
+__device__ __forceinline__ GateUp load_gate_up(const bf16_t *src, int half_n, int col_base, int lane) {
+  GateUp r;
+#pragma unroll
+  for (int f2 = 0; f2 < 2; ++f2)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int col = col_base + f2 * 32 + 8 * g + 4 * (lane >> 5);
+      const int cc = col < half_n ? col : 0;
+      r.gt[f2][g] = *reinterpret_cast<const bf16x4 *>(src + cc);
+      r.up[f2][g] = *reinterpret_cast<const bf16x4 *>(src + half_n + cc);
+    }
+  return r;
+}
 template <typename RowFn>
 __device__ __forceinline__ void store_wave_tile_swiglu_bwd(const f32x16 (&acc)[FR][FR], char *patch, RowFn dst_row,
                                                            const bf16_t *Hpre, bf16_t *dHpre, const float *row_scale,
@@ -150,58 +208,63 @@ __device__ __forceinline__ void store_wave_tile_swiglu_bwd(const f32x16 (&acc)[F
                                                            int row_base, int row_end, int lane) {
   __asm__ volatile("s_nop 15\n\ts_nop 15" ::: "memory");
   const size_t ld = (size_t)2 * half_n;
+  // the lane's own row in a fragment row (source of the pre-activations and of the routing weight); rows past the
+  // segment read its last row
+  auto own_row = [&](int fm) { return min(row_base + fm * 32 + (lane & 31), row_end - 1); };
+  RowStore pend;
+  pend.have = false;
+  GateUp in = load_gate_up(Hpre + (size_t)own_row(0) * ld, half_n, gcol, lane);
+  float scale_next = row_scale[own_row(0)];
 #pragma unroll
   for (int fm = 0; fm < FR; ++fm) {
-    const int grow = row_base + fm * 32 + (lane & 31);
-    const bool live = grow < row_end;
-    const int srow = live ? grow : row_end - 1;
-    const bf16_t *src = Hpre + (size_t)srow * ld;
-    const float scale = row_scale[srow];
     float dp = 0.f;
+    const float scale = scale_next;
+    int drow[4];      // destination rows of the lane's chunks in this fragment row (the rows are expert-sorted, never scattered)
+#pragma unroll
+    for (int it = 0; it < 4; ++it) drow[it] = dst_row(fm * 32 + it * 8 + (lane >> 3));
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
-      sched_fence();
-      bf16x4 gt[2][4], up[2][4];
-#pragma unroll
-      for (int f2 = 0; f2 < 2; ++f2)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int col = gcol + half * 64 + f2 * 32 + 8 * g + 4 * (lane >> 5);
-          const int cc = col < half_n ? col : 0;
-          gt[f2][g] = *reinterpret_cast<const bf16x4 *>(src + cc);
-          up[f2][g] = *reinterpret_cast<const bf16x4 *>(src + half_n + cc);
-        }
+      const GateUp cur = in;
+      if (fm * 2 + half + 1 < 2 * FR) {   // request the next 64 columns (or the next fragment row) now
+        const int nfm = half == 0 ? fm : fm + 1;
+        in = load_gate_up(Hpre + (size_t)own_row(nfm) * ld, half_n, gcol + (half == 0 ? 64 : 0), lane);
+        if (half == 1) scale_next = row_scale[own_row(nfm)];
+      }
       bf16x4 du[2][4];
+      pipe_block(pend, patch, lane, [&] {
 #pragma unroll
-      for (int f2 = 0; f2 < 2; ++f2)
+        for (int f2 = 0; f2 < 2; ++f2)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int col = gcol + half * 64 + f2 * 32 + 8 * g + 4 * (lane >> 5);
-          bf16x4 dg;
+          for (int g = 0; g < 4; ++g) {
+            const int col = gcol + half * 64 + f2 * 32 + 8 * g + 4 * (lane >> 5);
+            bf16x4 dg;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const float a = acc_read(acc[fm][half * 2 + f2][g * 4 + q]);
-            const float gate = (float)gt[f2][g][q], u = (float)up[f2][g][q];
-            const float sig = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gate));
-            const float silu = gate * sig;
-            if (col < half_n) dp = fmaf(a, silu * u, dp);
-            const float dh = scale * a;
-            dg[q] = (bf16_t)(dh * u * (sig + silu * (1.0f - sig)));
-            du[f2][g][q] = (bf16_t)(dh * silu);
+            for (int q = 0; q < 4; ++q) {
+              const float a = acc_read(acc[fm][half * 2 + f2][g * 4 + q]);
+              const float gate = (float)cur.gt[f2][g][q], u = (float)cur.up[f2][g][q];
+              const float sig = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gate));
+              const float silu = gate * sig;
+              if (col < half_n) dp = fmaf(a, silu * u, dp);
+              const float dh = scale * a;
+              dg[q] = (bf16_t)(dh * u * (sig + silu * (1.0f - sig)));
+              du[f2][g][q] = (bf16_t)(dh * silu);
+            }
+            *reinterpret_cast<bf16x4 *>(patch + (lane & 31) * EPI_ROW_BYTES + (f2 * 32 + 8 * g + 4 * (lane >> 5)) * 2) = dg;
           }
-          *reinterpret_cast<bf16x4 *>(patch + (lane & 31) * EPI_ROW_BYTES + (f2 * 32 + 8 * g + 4 * (lane >> 5)) * 2) = dg;
-        }
-      flush_patch(patch, dst_row, fm, dHpre, ld, 0, gcol + half * 64, half_n, lane);
+      }, drow, dHpre, ld, 0, gcol + half * 64, half_n);
+      pipe_block(pend, patch, lane, [&] {
 #pragma unroll
-      for (int f2 = 0; f2 < 2; ++f2)
+        for (int f2 = 0; f2 < 2; ++f2)
 #pragma unroll
-        for (int g = 0; g < 4; ++g)
-          *reinterpret_cast<bf16x4 *>(patch + (lane & 31) * EPI_ROW_BYTES + (f2 * 32 + 8 * g + 4 * (lane >> 5)) * 2) = du[f2][g];
-      flush_patch(patch, dst_row, fm, dHpre, ld, half_n, gcol + half * 64, half_n, lane);
+          for (int g = 0; g < 4; ++g)
+            *reinterpret_cast<bf16x4 *>(patch + (lane & 31) * EPI_ROW_BYTES + (f2 * 32 + 8 * g + 4 * (lane >> 5)) * 2) = du[f2][g];
+      }, drow, dHpre, ld, half_n, gcol + half * 64, half_n);
     }
     dp += __shfl_xor(dp, 32, 64);
-    if (live && lane < 32) dp_part[(size_t)grow * part_ld + part_col] = dp;
+    if (row_base + fm * 32 + lane < row_end && lane < 32) dp_part[(size_t)(row_base + fm * 32 + lane) * part_ld + part_col] = dp;
   }
+  sched_fence();
+  issue_row_store(pend, lane);
 }
 
 // A wavefront's 128 x 128 accumulators as fp32 into a 256-wide partial tile (chunks of a split contraction).
