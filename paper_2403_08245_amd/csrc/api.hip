@@ -422,20 +422,27 @@ int smoe_mlp_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
 
 // Workspace of the backward pass: dYbar [Tk,d_model] (later reused for dXbar), dH [Tk,d_expert],
 // dHpre [Tk,d_h].
-// Fused layout (bf16 SwiGLU through the persistent kernels): the unweighted and the weighted expert-sorted copies of
-// dY [Tk,d_model] each (the first one later holds Xbar, then dXbar), dHpre [Tk,d_h], the sorted routing weights [Tk]
-// and the slabs of dp [Tk, 2 * ceil(d_expert / 256)] fp32.
-struct MlpBwdFusedLayout {
-  size_t dybar_u, dybar_w, dhpre, gsorted, dp_part, total;
+// Backward passes that form dp in the epilogue of the W2^T product (bf16 through the persistent kernels).
+//   mode 1 (SwiGLU): the activation's derivative is applied there too; scratch = the unweighted and the weighted
+//     expert-sorted copies of dY [Tk,d_model] each (the first one later holds Xbar, then dXbar), dHpre [Tk,d_h].
+//   mode 2 (other activations): dp from the saved H; scratch = the unweighted sorted dY, then either the weighted copy or,
+//     when d_expert < d_model makes it the smaller tensor, the routing-weighted hidden rows Hw [Tk,d_expert] that let
+//     groupXTY form dW2 from the unweighted copy; dH [Tk,d_expert]; dHpre [Tk,d_h].
+//   both: the sorted routing weights [Tk] and the slabs of dp [Tk, 2 * ceil(d_expert / 256)] fp32.
+struct MlpBwdEpiLayout {
+  size_t dybar_u, second, dh, dhpre, gsorted, dp_part, total;
   int part_ld;
+  bool use_hw;
 };
-static MlpBwdFusedLayout mlp_bwd_fused_layout(size_t es, size_t Tk, int d_model, int d_expert) {
-  MlpBwdFusedLayout L;
+static MlpBwdEpiLayout mlp_bwd_epi_layout(int mode, size_t es, size_t Tk, int d_model, int d_expert, int d_h) {
+  MlpBwdEpiLayout L;
   size_t off = 0;
   L.part_ld = 2 * ceil_div(d_expert, 256);
+  L.use_hw = mode == 2 && d_expert < d_model;
   L.dybar_u = off;  off += align256(Tk * d_model * es);
-  L.dybar_w = off;  off += align256(Tk * d_model * es);
-  L.dhpre = off;    off += align256(Tk * 2 * (size_t)d_expert * es);
+  L.second = off;   off += align256(Tk * (size_t)(L.use_hw ? d_expert : d_model) * es);
+  L.dh = off;       off += mode == 2 ? align256(Tk * (size_t)d_expert * es) : 0;
+  L.dhpre = off;    off += align256(Tk * (size_t)d_h * es);
   L.gsorted = off;  off += align256(Tk * sizeof(float));
   L.dp_part = off;  off += align256(Tk * (size_t)L.part_ld * sizeof(float));
   L.total = off + S2S_TAIL_WS_BYTES;
@@ -445,17 +452,17 @@ static MlpBwdFusedLayout mlp_bwd_fused_layout(size_t es, size_t Tk, int d_model,
 size_t smoe_mlp_bwd_workspace_bytes(smoe_dtype dtype, smoe_act act, int T, int k, int d_model, int d_expert) {
   if (!dtype_ok(dtype) || T < 0 || k < 1 || d_model < 1 || d_expert < 1) return 0;
   size_t es = dtype_size(dtype), Tk = (size_t)T * k;
-  size_t plain = align256(Tk * d_model * es) + align256(Tk * d_expert * es) + align256(Tk * hidden_width(act, d_expert) * es) +
-                 S2S_TAIL_WS_BYTES;
-  if (dtype != SMOE_BF16 || act != SMOE_ACT_SWIGLU) return plain;
-  size_t fused = mlp_bwd_fused_layout(es, Tk, d_model, d_expert).total;   // whichever path the shape takes fits
-  return fused > plain ? fused : plain;
+  const int d_h = hidden_width(act, d_expert);
+  size_t plain = align256(Tk * d_model * es) + align256(Tk * d_expert * es) + align256(Tk * d_h * es) + S2S_TAIL_WS_BYTES;
+  if (dtype != SMOE_BF16) return plain;
+  size_t epi = mlp_bwd_epi_layout(act == SMOE_ACT_SWIGLU ? 1 : 2, es, Tk, d_model, d_expert, d_h).total;
+  return epi > plain ? epi : plain;   // whichever path the shape takes fits
 }
 
-// Whether the backward pass of this shape computes dp in the input-gradient product's epilogue, so that the forward's
-// unweighted Yhat need not be kept for it.
-static bool mlp_bwd_fused(const smoe_ctx *ctx, smoe_dtype dtype, smoe_act act, int Tk, int E, int d_model, int d_expert) {
-  if (dtype != SMOE_BF16 || act != SMOE_ACT_SWIGLU || ctx->kernel_mode != 0 || Tk < 1) return false;
+// How the backward pass of this shape runs: 0 = Alg. 2 step by step (dp from the forward's saved Yhat), 1 / 2 = dp in the
+// epilogue of the W2^T product as described above (the forward's unweighted Yhat is then not needed).
+static int mlp_bwd_mode(const smoe_ctx *ctx, smoe_dtype dtype, smoe_act act, int Tk, int E, int d_model, int d_expert) {
+  if (dtype != SMOE_BF16 || ctx->kernel_mode != 0 || Tk < 1) return 0;
   S2SArgs x;
   x.A = x.W = nullptr;  x.C = nullptr;
   x.a_map = RowMap{nullptr, 1};  x.c_map = RowMap{nullptr, 1};
@@ -463,13 +470,18 @@ static bool mlp_bwd_fused(const smoe_ctx *ctx, smoe_dtype dtype, smoe_act act, i
   x.K = d_model;  x.N = d_expert;  x.ldw = d_model;  x.w_stride = (size_t)d_expert * d_model;  x.trans_w = 1;
   x.tail_ws = nullptr;  x.H = nullptr;
   x.grid = ctx->stream_grid;
-  x.Hpre_in = (const void *)1;  x.row_scale = (const float *)1;  x.dp_part = (float *)1;   // only tested for presence
-  return s2s_stream_swiglu_bwd_supported(x);
+  x.row_scale = (const float *)1;  x.dp_part = (float *)1;   // only tested for presence
+  if (act == SMOE_ACT_SWIGLU) {
+    x.Hpre_in = (const void *)1;
+    return s2s_stream_swiglu_bwd_supported(x) ? 1 : 0;
+  }
+  x.H_in = (const void *)1;
+  return s2s_stream_dp_supported(x) ? 2 : 0;
 }
 
 int smoe_mlp_saves_yhat(smoe_ctx *ctx, smoe_dtype dtype, smoe_act act, int T, int k, int E, int d_model, int d_expert) {
   if (!ctx || !dtype_ok(dtype) || T < 0 || k < 1 || E < 1 || d_model < 1 || d_expert < 1) return SMOE_ERR_INVALID_ARG;
-  return mlp_bwd_fused(ctx, dtype, act, T * k, E, d_model, d_expert) ? 0 : 1;
+  return mlp_bwd_mode(ctx, dtype, act, T * k, E, d_model, d_expert) ? 0 : 1;
 }
 
 int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, const void *dY, const void *X, int T,
@@ -495,26 +507,36 @@ int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
     DWArgs z2{nullptr, nullptr, dW2, r->expert_offsets, r->E, 0, d_expert, d_model};
     return launch_dw_plain(s, dtype, z2);
   }
-  const bool fused = mlp_bwd_fused(ctx, dtype, act, Tk, r->E, d_model, d_expert);
-  if (!dY || !X || !W1 || !W2 || !gates || !saved_Hpre || !saved_H || (!saved_Yhat && !fused) || !dX || !dgates)
+  const int mode = mlp_bwd_mode(ctx, dtype, act, Tk, r->E, d_model, d_expert);
+  if (!dY || !X || !W1 || !W2 || !gates || !saved_Hpre || !saved_H || (!saved_Yhat && !mode) || !dX || !dgates)
     return SMOE_ERR_INVALID_ARG;
   if (!aligned16(dY) || !aligned16(X) || !aligned16(W1) || !aligned16(W2) || !aligned16(saved_Hpre) ||
       !aligned16(saved_H) || (saved_Yhat && !aligned16(saved_Yhat)) || !aligned16(dX) || !aligned16(dW1) || !aligned16(dW2))
     return SMOE_ERR_UNSUPPORTED;
-  if (fused) {
-    // Alg. 2 for both ParallelLinears with the activation's derivative and dp taken in the epilogue of the
-    // W2^T product: that product runs on the UNWEIGHTED sorted copy of dY, so its fp32 accumulators are dH / p and
-    // dp[row] = <acc, H[row]> needs neither the forward's Yhat nor a division by a routing weight; groupXTY for dW2
-    // takes the weighted copy.
-    const MlpBwdFusedLayout L = mlp_bwd_fused_layout(es, (size_t)Tk, d_model, d_expert);
+  if (mode) {
+    // Alg. 2 for both ParallelLinears with dp taken in the epilogue of the W2^T product: that product runs on the
+    // UNWEIGHTED sorted copy of dY, so its fp32 accumulators are dH / p and dp[row] = <acc, H[row]> needs neither the
+    // forward's Yhat nor a division by a routing weight.
+    const MlpBwdEpiLayout L = mlp_bwd_epi_layout(mode, es, (size_t)Tk, d_model, d_expert, d_h);
     char *base = (char *)ws;
-    void *dYu = base + L.dybar_u, *dYw = base + L.dybar_w, *dHpre = base + L.dhpre;
+    void *dYu = base + L.dybar_u, *second = base + L.second, *dH = base + L.dh, *dHpre = base + L.dhpre;
     float *gsorted = (float *)(base + L.gsorted), *dp_part = (float *)(base + L.dp_part);
     float *tail_ws = (float *)(base + L.total - S2S_TAIL_WS_BYTES);
-    rc = launch_group_pair(s, dtype, dY, r->sorted_scattered_idxs, k, gates, dYu, dYw, gsorted, Tk, d_model);
+    if (L.use_hw) {      // one sorted copy of dY; the routing weights go into Hw instead
+      rc = launch_group(s, dtype, dY, r->sorted_scattered_idxs, k, nullptr, dYu, Tk, d_model);
+      if (rc != SMOE_OK) return rc;
+      rc = launch_sorted_weights(s, r->sorted_scattered_idxs, gates, gsorted, Tk);
+    } else {             // plain and weighted sorted copies in one pass (groupXTY for dW2 takes the weighted one)
+      rc = launch_group_pair(s, dtype, dY, r->sorted_scattered_idxs, k, gates, dYu, second, gsorted, Tk, d_model);
+    }
     if (rc != SMOE_OK) return rc;
-    S2SArgs x2 = make_s2s(dYu, W2, dHpre, r, d_expert, d_model, true, true, 1, true);   // dHpre = sigma'(Hpre) p (dYu W2^T)
-    x2.Hpre_in = saved_Hpre;
+    S2SArgs x2 = make_s2s(dYu, W2, mode == 1 ? dHpre : dH, r, d_expert, d_model, true, true, 1, true);
+    if (mode == 1) {
+      x2.Hpre_in = saved_Hpre;           // dHpre = sigma'(Hpre) p (dYu W2^T) straight from the accumulators
+    } else {
+      x2.H_in = saved_H;                 // dH = p (dYu W2^T), Hw = p H
+      x2.Hw_out = L.use_hw ? second : nullptr;
+    }
     x2.row_scale = gsorted;
     x2.dp_part = dp_part;
     x2.grid = ctx->stream_grid;
@@ -523,7 +545,12 @@ int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
     if (rc != SMOE_OK) return rc;
     rc = launch_dp_reduce(s, dp_part, L.part_ld, r->sorted_scattered_idxs, dgates, Tk);
     if (rc != SMOE_OK) return rc;
-    DWArgs w2{saved_H, dYw, dW2, r->expert_offsets, r->E, Tk, d_expert, d_model};
+    if (mode == 2) {
+      rc = launch_act_bwd(s, dtype, act, saved_Hpre, dH, dHpre, Tk, d_expert);
+      if (rc != SMOE_OK) return rc;
+    }
+    DWArgs w2{L.use_hw ? (const void *)second : saved_H, L.use_hw ? (const void *)dYu : (const void *)second, dW2,
+              r->expert_offsets, r->E, Tk, d_expert, d_model};
     w2.split_ws = tail_ws;
     rc = run_dw(ctx, s, dtype, w2);
     if (rc != SMOE_OK) return rc;

@@ -77,6 +77,8 @@ int launch_group_pair(hipStream_t s, smoe_dtype dt, const void *in, const int32_
 // dg[o[i]] = sum_c part[i, c] (c ascending): finishes the routing-weight gradient left in slabs by the fused
 // SwiGLU backward epilogue.
 int launch_dp_reduce(hipStream_t s, const float *part, int ld, const int32_t *o, float *dg, int Tk);
+// g_sorted[i] = g[o[i]]: the routing weight of every expert-sorted row
+int launch_sorted_weights(hipStream_t s, const int32_t *o, const float *g, float *g_sorted, int Tk);
 // dg[s] = <dY[s / kp], Yhat[s]>
 int launch_rowdot(hipStream_t s, smoe_dtype dt, const void *dY, const void *Yhat, float *dg, int Tk, int kp, int d);
 
@@ -112,6 +114,12 @@ struct S2SArgs {      // C[out(i), :] = A[in(i), :] * op(W[e(i)])   for sorted r
   const void *Hpre_in = nullptr;
   const float *row_scale = nullptr;
   float *dp_part = nullptr;
+  // The same idea for any activation (still the W2^T product on unweighted sorted rows): with H_in [Tk, N] (the saved
+  // hidden activations), row_scale and dp_part set and Hpre_in NULL, the epilogue writes C = dH = row_scale * acc, the
+  // slabs of dp = <acc, H>, and, when Hw_out [Tk, N] is given, Hw = row_scale * H (the routing-weighted hidden rows
+  // that let groupXTY take the unweighted sorted dY for dW2 as well).  The activation's derivative stays a row kernel.
+  const void *H_in = nullptr;
+  void *Hw_out = nullptr;
 };
 struct DWArgs {       // dW[e] = sum_{i in segment e} A[i, :]^T B[i, :]   (both operands expert-sorted)
   const void *A;      // [Tk, M]
@@ -140,6 +148,7 @@ constexpr size_t S2S_TAIL_WS_BYTES = (size_t)256 * 256 * 256 * sizeof(float);   
 bool s2s_stream_supported(const S2SArgs &a);
 bool s2s_stream_swiglu_supported(const S2SArgs &a);
 bool s2s_stream_swiglu_bwd_supported(const S2SArgs &a);
+bool s2s_stream_dp_supported(const S2SArgs &a);
 int launch_s2s_stream(hipStream_t s, const S2SArgs &a);
 // Small-batch (decoding) forward products: 32-row tiles, one wavefront each, bound by the weight stream.
 // Takes a.H like the persistent kernel (fused SwiGLU).

@@ -280,6 +280,18 @@ int launch_group_pair(hipStream_t s, smoe_dtype dt, const void *in, const int32_
                          : group_pair_t<float>(s, in, o, fan, g, out_plain, out_weighted, g_sorted, Tk, d);
 }
 
+__global__ void __launch_bounds__(256) sorted_weights_kernel(const int32_t *__restrict__ o, const float *__restrict__ g,
+                                                             float *__restrict__ g_sorted, int Tk) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < Tk) g_sorted[i] = g[o[i]];
+}
+int launch_sorted_weights(hipStream_t s, const int32_t *o, const float *g, float *g_sorted, int Tk) {
+  if (!Tk) return SMOE_OK;
+  hipLaunchKernelGGL(sorted_weights_kernel, dim3(ceil_div(Tk, 256)), dim3(256), 0, s, o, g, g_sorted, Tk);
+  SMOE_LAUNCH_CHECK();
+  return SMOE_OK;
+}
+
 int launch_dp_reduce(hipStream_t s, const float *part, int ld, const int32_t *o, float *dg, int Tk) {
   if (!Tk) return SMOE_OK;
   hipLaunchKernelGGL(dp_reduce_kernel, dim3(ceil_div(Tk, 256)), dim3(256), 0, s, part, ld, o, dg, Tk);

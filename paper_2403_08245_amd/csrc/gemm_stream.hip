@@ -267,6 +267,83 @@ __device__ __forceinline__ void store_wave_tile_swiglu_bwd(const f32x16 (&acc)[F
   issue_row_store(pend, lane);
 }
 
+// The activation-agnostic form: the accumulators hold dH / p; the lane fetches the saved hidden activations H of its
+// row and column groups, adds <acc, H> to the row's slab of dp, and writes dH = p * acc (and Hw = p * H when asked).
+template <typename RowFn>
+__device__ __forceinline__ void store_wave_tile_dp(const f32x16 (&acc)[FR][FR], char *patch, RowFn dst_row, const bf16_t *H,
+                                                   bf16_t *dH, bf16_t *Hw, const float *row_scale, float *dp_part, int part_ld,
+                                                   int part_col, int n, int gcol, int row_base, int row_end, int lane) {
+  __asm__ volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+  auto own_row = [&](int fm) { return min(row_base + fm * 32 + (lane & 31), row_end - 1); };
+  auto load_h = [&](int fm, int half, bf16x4 (&h)[2][4]) {
+    const bf16_t *src = H + (size_t)own_row(fm) * n;
+#pragma unroll
+    for (int f2 = 0; f2 < 2; ++f2)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = gcol + half * 64 + f2 * 32 + 8 * g + 4 * (lane >> 5);
+        h[f2][g] = *reinterpret_cast<const bf16x4 *>(src + (col < n ? col : 0));
+      }
+  };
+  RowStore pend;
+  pend.have = false;
+  bf16x4 nxt[2][4];
+  load_h(0, 0, nxt);
+  float scale_next = row_scale[own_row(0)];
+#pragma unroll
+  for (int fm = 0; fm < FR; ++fm) {
+    float dp = 0.f;
+    const float scale = scale_next;
+    int drow[4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) drow[it] = dst_row(fm * 32 + it * 8 + (lane >> 3));
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      bf16x4 cur[2][4];
+#pragma unroll
+      for (int f2 = 0; f2 < 2; ++f2)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) cur[f2][g] = nxt[f2][g];
+      if (fm * 2 + half + 1 < 2 * FR) {   // request the next 64 columns (or the next fragment row) now
+        load_h(half == 0 ? fm : fm + 1, half == 0 ? 1 : 0, nxt);
+        if (half == 1) scale_next = row_scale[own_row(fm + 1)];
+      }
+      pipe_block(pend, patch, lane, [&] {
+#pragma unroll
+        for (int f2 = 0; f2 < 2; ++f2)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int col = gcol + half * 64 + f2 * 32 + 8 * g + 4 * (lane >> 5);
+            bf16x4 v;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const float a = acc_read(acc[fm][half * 2 + f2][g * 4 + q]);
+              if (col < n) dp = fmaf(a, (float)cur[f2][g][q], dp);
+              v[q] = (bf16_t)(scale * a);
+            }
+            *reinterpret_cast<bf16x4 *>(patch + (lane & 31) * EPI_ROW_BYTES + (f2 * 32 + 8 * g + 4 * (lane >> 5)) * 2) = v;
+          }
+      }, drow, dH, (size_t)n, 0, gcol + half * 64, n);
+      if (Hw)
+        pipe_block(pend, patch, lane, [&] {
+#pragma unroll
+          for (int f2 = 0; f2 < 2; ++f2)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              bf16x4 v;
+#pragma unroll
+              for (int q = 0; q < 4; ++q) v[q] = (bf16_t)(scale * (float)cur[f2][g][q]);
+              *reinterpret_cast<bf16x4 *>(patch + (lane & 31) * EPI_ROW_BYTES + (f2 * 32 + 8 * g + 4 * (lane >> 5)) * 2) = v;
+            }
+        }, drow, Hw, (size_t)n, 0, gcol + half * 64, n);
+    }
+    dp += __shfl_xor(dp, 32, 64);
+    if (row_base + fm * 32 + lane < row_end && lane < 32) dp_part[(size_t)(row_base + fm * 32 + lane) * part_ld + part_col] = dp;
+  }
+  sched_fence();
+  issue_row_store(pend, lane);
+}
+
 // A wavefront's 128 x 128 accumulators as fp32 into a 256-wide partial tile (chunks of a split contraction).
 __device__ __forceinline__ void store_wave_partial(const f32x16 (&acc)[FR][FR], float *dst, int lane) {
   __asm__ volatile("s_nop 15\n\ts_nop 15" ::: "memory");
@@ -429,15 +506,17 @@ template <bool TRANS_W> struct S2SStreamOps {
 };
 
 // ACT 1: fused SwiGLU keeping the pre-activation, 2: without, 3: fused SwiGLU derivative and dp (the W2^T input-gradient
-// product of Alg. 3's backward, see store_wave_tile_swiglu_bwd).  STATIC4: the contraction is a multiple of four
+// product of Alg. 3's backward, see store_wave_tile_swiglu_bwd), 4: dp from the saved H in that product's epilogue for any
+// activation (store_wave_tile_dp).  STATIC4: the contraction is a multiple of four
 // half-steps, so every tile starts in LDS stage 0 and the loop is written out four slots at a time with the
 // stage as a compile-time constant: all LDS addresses become a loop-invariant register plus an immediate.
 template <bool TRANS_W, bool SCATTER_OUT, int ACT = 0, bool STATIC4 = false>
 __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int tiles_n, int group_m, uint32_t magic_a) {
   constexpr bool SWIGLU = ACT == 1 || ACT == 2;
   constexpr bool SWIGLU_BWD = ACT == 3;
+  constexpr bool DP_EPI = ACT == 4;
   static_assert(!SWIGLU || (!TRANS_W && !SCATTER_OUT), "the fused activation belongs to the forward, sorted-output product");
-  static_assert(!SWIGLU_BWD || (TRANS_W && !SCATTER_OUT), "the fused derivative belongs to the W^T product with sorted rows in and out");
+  static_assert(!(SWIGLU_BWD || DP_EPI) || (TRANS_W && !SCATTER_OUT), "the fused derivative belongs to the W^T product with sorted rows in and out");
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   __shared__ int s_off[MAX_E + 1];
   // Order indices of the rows of up to four open tiles.  With the shortest contraction the kernel takes (three
@@ -649,6 +728,9 @@ __global__ void __launch_bounds__(NTHREADS, 1) s2s_stream_kernel(S2SArgs a, int 
     else if (SWIGLU_BWD)
       store_wave_tile_swiglu_bwd(acc, patch, dst_row, (const bf16_t *)a.Hpre_in, (bf16_t *)a.C, a.row_scale, a.dp_part, 2 * tiles_n,
                                  (ct.n0 / TB) * 2 + wn, a.N, ct.n0 + wn * (TB / 2), rbase, ct.row_end, lane);
+    else if (DP_EPI)
+      store_wave_tile_dp(acc, patch, dst_row, (const bf16_t *)a.H_in, (bf16_t *)a.C, (bf16_t *)a.Hw_out, a.row_scale, a.dp_part, 2 * tiles_n,
+                         (ct.n0 / TB) * 2 + wn, a.N, ct.n0 + wn * (TB / 2), rbase, ct.row_end, lane);
     else if (ct.part >= 0)
       store_wave_partial(acc, a.tail_ws + (size_t)ct.part * TB * TB + (size_t)(wm * (TB / 2)) * TB + wn * (TB / 2), lane);
     else
@@ -1000,15 +1082,24 @@ bool s2s_stream_swiglu_bwd_supported(const S2SArgs &a) {
          a.N % 8 == 0;
 }
 
+bool s2s_stream_dp_supported(const S2SArgs &a) {
+  return s2s_stream_supported(a) && a.trans_w && !a.c_map.o && !a.a_map.o && a.H_in && !a.Hpre_in && a.row_scale && a.dp_part &&
+         a.N % 8 == 0;
+}
+
 bool s2s_stream_swiglu_supported(const S2SArgs &a) {
   return s2s_stream_supported(a) && !a.trans_w && !a.c_map.o && a.H && a.N % 16 == 0;
 }
 
 int launch_s2s_stream(hipStream_t s, const S2SArgs &a) {
   const bool scatter_out = a.c_map.o != nullptr;
-  if (a.dp_part) {
+  if (a.dp_part && a.Hpre_in) {
     if (!s2s_stream_swiglu_bwd_supported(a)) return SMOE_ERR_UNSUPPORTED;
     return launch_s2s_stream_cfg<true, false, 3>(s, a);
+  }
+  if (a.dp_part) {
+    if (!s2s_stream_dp_supported(a)) return SMOE_ERR_UNSUPPORTED;
+    return launch_s2s_stream_cfg<true, false, 4>(s, a);
   }
   if (a.H) {
     if (!s2s_stream_swiglu_supported(a)) return SMOE_ERR_UNSUPPORTED;
@@ -1038,6 +1129,7 @@ int init_stream_kernels() {
   if (rc == SMOE_OK) rc = init_s2s_pair<false, false, 1>();
   if (rc == SMOE_OK) rc = init_s2s_pair<false, false, 2>();
   if (rc == SMOE_OK) rc = init_s2s_pair<true, false, 3>();
+  if (rc == SMOE_OK) rc = init_s2s_pair<true, false, 4>();
   if (rc == SMOE_OK) rc = set_lds_limit(dw_stream_kernel, STREAM_LDS_BYTES);
   return rc;
 }

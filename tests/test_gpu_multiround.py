@@ -172,20 +172,27 @@ def test_fused_swiglu_forward_every_row_over_several_rounds(smoe, d_model, d_exp
     assert bool(torch.isfinite(Y.float()).all())
 
 
-def test_fused_swiglu_backward_over_several_rounds(smoe):
-    """The W2^T input-gradient product with the activation's derivative and the routing-weight gradient in its
-    epilogue, 500+ tiles.  dHpre itself is scratch; what it feeds is compared: dgates and dX on tokens drawn from
-    every tile of every expert, two columns pairs of dW1 and two rows of dW2 from every 256-unit tile for every
-    expert (each sums over all the expert's rows), and every output must be free of the poison the workspace
-    and outputs start with.  The forward's unweighted second product is not kept for such shapes."""
-    cfg = si.custom("fused-bwd-rounds", T=4096, d_model=128, d_expert=4096, E=8, k=2, act=si.ACT_SWIGLU, dtype="bf16",
-                    zipf_s=1.2)
+@pytest.mark.parametrize("act,T,d_model,d_expert", [
+    pytest.param(si.ACT_SWIGLU, 4096, 128, 4096, id="swiglu-derivative-in-epilogue"),
+    pytest.param(si.ACT_GELU, 4096, 128, 4096, id="gelu-two-sorted-copies"),
+    pytest.param(si.ACT_GELU, 16384, 1280, 1024, id="gelu-weighted-hidden-rows"),
+    pytest.param(si.ACT_NONE, 4096, 160, 3848, id="identity-ragged-width"),
+])
+def test_backward_with_dp_in_epilogue_over_several_rounds(smoe, act, T, d_model, d_expert):
+    """The W2^T input-gradient product with the routing-weight gradient (and for SwiGLU the activation's derivative)
+    in its epilogue, 500+ tiles; for the other activations the two ways of forming dW2 (a weighted second sorted copy
+    of dY, or routing-weighted hidden rows when those are narrower).  The intermediate tensors are scratch; what they
+    feed is compared: dgates and dX on tokens drawn from every tile of every expert, two column pairs of dW1 and two
+    rows of dW2 from every 256-unit tile for every expert (each sums over all the expert's rows), and every output
+    must be free of the poison the workspace and outputs start with.  The forward's unweighted second product is not
+    kept for such shapes."""
+    cfg = si.custom("bwd-epilogue-rounds", T=T, d_model=d_model, d_expert=d_expert, E=8, k=2, act=act, dtype="bf16", zipf_s=1.2)
     case = si.mlp_case(cfg, 23)
     ei, g, se, o, off = oracle_routing(case["logits"], cfg.k, cfg.E)
     gi, gg = smoe.topk_gate(case["logits"].cuda(), cfg.k)
     r = smoe.route(gi, cfg.E)
     assert np.array_equal(r.sorted_scattered_idxs.cpu().numpy(), o)
-    tiles = _m_tiles(off) * (cfg.d_expert // TB)
+    tiles = _m_tiles(off) * -(-cfg.d_expert // TB)
     _log(f"input-gradient tiles {tiles}")
     assert tiles >= 2 * GRID
     X, W1, W2, dY = (case[n].cuda() for n in ("X", "W1", "W2", "dY"))
@@ -198,7 +205,7 @@ def test_fused_swiglu_backward_over_several_rounds(smoe):
     g64 = oracle_gates_f32(g)
     X64, W164, W264, dY64 = (si.as_f64(case[n]) for n in ("X", "W1", "W2", "dY"))
     rng = np.random.default_rng(9)
-    rows = np.concatenate([rng.choice(np.arange(a, min(a + TB, int(off[e + 1]))), size=min(6, int(off[e + 1]) - a), replace=False)
+    rows = np.concatenate([rng.choice(np.arange(a, min(a + TB, int(off[e + 1]))), size=min(6 if T <= 4096 else 2, int(off[e + 1]) - a), replace=False)
                            for e in range(cfg.E) for a in range(int(off[e]), int(off[e + 1]), TB)])
     toks = np.unique(o[rows] // cfg.k)
     _log(f"{len(toks)} tokens from {len(rows)} sampled rows")
@@ -211,7 +218,8 @@ def test_fused_swiglu_backward_over_several_rounds(smoe):
     r1, g1, r2, g2 = [], [], [], []
     for e in range(cfg.E):
         r1.append(oracle.mlp_dW1_cols(dY64, X64, W164, W264, ei, g64, cfg.act, e, units))
-        g1.append(torch.stack([dW1[e][:, ut].T, dW1[e][:, ut + cfg.d_expert].T], 1).float().cpu().numpy())
+        cols = [ut] + ([ut + cfg.d_expert] if act == si.ACT_SWIGLU else [])
+        g1.append(torch.stack([dW1[e][:, c].T for c in cols], 1).float().cpu().numpy())
         r2.append(oracle.mlp_dW2_rows(dY64, X64, W164, W264, ei, g64, cfg.act, e, units))
         g2.append(dW2[e][ut].float().cpu().numpy())
     assert_close(np.stack(g1), np.stack(r1), torch.bfloat16, "dW1 (two unit pairs per tile)")
