@@ -103,3 +103,44 @@ def test_guarded_allocator_poisons_and_catches_stray_writes(monkeypatch):
     c.live[0][0][GuardedAllocator.GUARD - 1] = 0         # last byte in front of it
     with pytest.raises(AssertionError, match="in front"):
         c.check()
+
+
+def test_every_entry_point_rejects_a_null_context_without_touching_the_gpu():
+    """No entry point throws or aborts: with no context each one returns SMOE_ERR_INVALID_ARG before it looks at any
+    pointer (this runs on a machine with no GPU), and every status value has a message."""
+    import ctypes
+    import paper_2403_08245_amd as m
+    lib = m.lib
+    calls = {
+        "smoe_set_kernel_mode": (None, 0), "smoe_set_clock_probe": (None, None),
+        "smoe_topk_gate": (None, None, None, 4, 4, 2, None, None),
+        "smoe_topk_gate_bwd": (None, None, None, None, None, 4, 4, 2, None),
+        "smoe_route": (None, None, None, 4, 2, 4, None, None, None, None, 0),
+        "smoe_route_noalloc": (None, None, None, 4, 2, 4, None, None, None),
+        "smoe_group": (None, None, 1, None, 8, None, 1, None, None),
+        "smoe_plinear_fwd": (None, None, 1, None, 4, 8, None, 8, None, 2, None, 0, 0, 0, None, None),
+        "smoe_plinear_bwd": (None, None, 1, None, None, 4, 8, None, 8, None, None, 2, None, 0, 0, 0, None, None, None, None, 0),
+        "smoe_plinear_act_fwd": (None, None, 1, 2, None, 4, 8, 8, None, None, 2, None, None, None, 0),
+        "smoe_mlp_fwd": (None, None, 1, 2, None, 4, 8, 8, None, None, None, 2, None, None, None, None, None, None, 0),
+        "smoe_mlp_bwd": (None, None, 1, 2, None, None, 4, 8, 8, None, None, None, 2, None, None, None, None, None, None, None,
+                         None, None, 0),
+        "smoe_mlp_saves_yhat": (None, 1, 2, 4, 2, 4, 8, 8),
+        "smoe_attention_fwd": (None, None, 1, None, None, None, 1, 4, 1, 1, 128, None, None),
+        "smoe_attention_bwd": (None, None, 1, None, None, None, None, None, None, 1, 4, 1, 1, 128, None, None, None, None, 0),
+        "smoe_momha_fwd": (None, None, 1, None, 1, 4, 8, 1, 128) + (None,) * 5 + (2,) + (None,) * 9 + (0,),
+        "smoe_momha_bwd": (None, None, 1, None, None, 1, 4, 8, 1, 128) + (None,) * 5 + (2,) + (None,) * 14 + (0,),
+    }
+    declared = set(m.EXPORTS) - {"smoe_create", "smoe_destroy", "smoe_strerror", "smoe_abi_version"}
+    declared = {n for n in declared if not n.endswith("_workspace_bytes")}
+    assert declared == set(calls), declared ^ set(calls)
+    for name, args in calls.items():
+        fn = getattr(lib, name)
+        fn.restype = ctypes.c_int
+        assert fn(*args) == -1, name
+    assert lib.smoe_create(None, 0) == -1
+    lib.smoe_destroy(None)
+    texts = {lib.smoe_strerror(c) for c in (0, -1, -2, -3, -4, -5)}
+    assert len(texts) == 6 and lib.smoe_strerror(-99) not in texts
+    # size queries answer 0 for shapes they cannot serve instead of failing
+    assert lib.smoe_route_workspace_bytes(-1, 2, 4) == 0 and lib.smoe_mlp_bwd_workspace_bytes(1, 2, 4, 0, 8, 8) == 0
+    assert lib.smoe_plinear_act_fwd_workspace_bytes(7, 2, 4, 2, 8, 8, 1) == 0

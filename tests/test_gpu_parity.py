@@ -308,6 +308,41 @@ def test_mlp_k1_and_k_equals_E(smoe):
     _mlp_parity(smoe, si.custom("kE", T=50, d_model=64, d_expert=32, E=4, k=4, act=si.ACT_GELU, dtype="f32"), 6)
 
 
+@pytest.mark.parametrize("act", [si.ACT_SWIGLU, si.ACT_GELU])
+@pytest.mark.parametrize("k", [1, 2])
+def test_routing_weight_gradient_with_vanishing_weights(smoe, act, k):
+    """dgates where the persistent kernels form it in a product's epilogue (contraction >= 96): k = 1 (every weight is
+    exactly 1), and k = 2 with half of the tokens routed so lopsidedly that their second weight is exactly 0 in fp32 --
+    its gradient <dY_t, Yhat> is still a plain dot product of order one, and no step may divide by the weight."""
+    cfg = si.custom(f"dp-k{k}", T=700, d_model=128, d_expert=160, E=6, k=k, act=act, dtype="bf16")
+    case = si.mlp_case(cfg, 19)
+    logits = case["logits"].clone()
+    logits[::2, 3] += 200.0                       # exp(-200) underflows: the other kept expert's weight is 0
+    ei, g, se, o, off = oracle_routing(logits, cfg.k, cfg.E)
+    gi, gg = smoe.topk_gate(logits.cuda(), cfg.k)
+    assert np.array_equal(gi.cpu().numpy(), ei) and np.abs(gg.cpu().numpy() - g).max() <= 1e-6
+    g32 = oracle_gates_f32(g)
+    if k == 2:
+        assert (g32[::2, 1] == 0).all() and (gg.cpu().numpy()[::2, 1] == 0).all()
+    r = smoe.route(gi, cfg.E)
+    X, W1, W2, dY = (case[n].cuda() for n in ("X", "W1", "W2", "dY"))
+    Y, buf = smoe.mlp_fwd(X, W1, W2, r, cfg.k, gg, cfg.act)
+    assert buf.Yhat is None                        # this shape does not keep the unweighted second product
+    dX, dW1, dW2, dg = smoe.mlp_bwd(dY, X, W1, W2, r, cfg.k, gg, cfg.act, buf)
+    X64, W164, W264, dY64 = (si.as_f64(case[n]) for n in ("X", "W1", "W2", "dY"))
+    ref = oracle.mlp_bwd(dY64, X64, W164, W264, ei, g32, cfg.act)
+    td = torch.bfloat16
+    assert_close(dg, ref["dgates"], td, "dgates")
+    if k == 2:
+        zero_w = ref["dgates"][::2, 1]
+        assert np.abs(zero_w).max() > 0.1           # the gradient of a vanished weight is not small
+        assert np.abs(dg.cpu().numpy()[::2, 1] - zero_w).max() <= TOL[td] * np.abs(ref["dgates"]).max()
+    assert_close(dX, ref["dX"], td, "dX")
+    assert_close(dW1, ref["dW1"], td, "dW1")
+    assert_close(dW2, ref["dW2"], td, "dW2")
+    assert_close(Y, oracle.mlp_fwd(X64, W164, W264, ei, g32, cfg.act)["Y"], td, "Y")
+
+
 def test_mlp_is_deterministic(smoe):
     cfg = si.CONFIGS["C3-small"]
     case, (X, W1, W2, dYc, r, gg) = _mlp_parity(smoe, cfg, 9)
@@ -369,6 +404,58 @@ def test_mlp_empty_batch(smoe):
     buf0.dW1.fill_(7.0); buf0.dW2.fill_(7.0)
     dX0, dW1, dW2, dg0 = smoe.mlp_bwd(X0, X0, W1, W2, r0, cfg.k, g0, cfg.act, buf0)
     assert Y0.shape[0] == 0 and float(dW1.abs().max()) == 0.0 and float(dW2.abs().max()) == 0.0
+
+
+def test_argument_errors_leave_nothing_enqueued(smoe):
+    """Shape, argument and workspace errors are found before the first launch: the outputs of a refused call still hold
+    the pattern they were filled with (checked through the C ABI, with undersized / misaligned workspaces, a routing
+    problem with more experts than the sort keeps counters for, and inconsistent row counts)."""
+    import ctypes
+    lib, cx = smoe.lib, smoe.ctx()
+    stream = torch.cuda.current_stream().cuda_stream
+    cfg = si.CONFIGS["C3-small"]
+    case = si.mlp_case(cfg, 0)
+    gi, gg = smoe.topk_gate(case["logits"].cuda(), cfg.k)
+    r = smoe.route(gi, cfg.E)
+    rc_ = r.c()
+    X, W1, W2, dY = (case[n].cuda() for n in ("X", "W1", "W2", "dY"))
+    mark = lambda *shape: torch.full(shape, 7.0, dtype=torch.bfloat16, device="cuda")
+    Y, Hpre, H = mark(cfg.T, cfg.d_model), mark(cfg.Tk, cfg.d_h), mark(cfg.Tk, cfg.d_expert)
+    need = lib.smoe_mlp_fwd_workspace_bytes(1, cfg.act, cfg.T, cfg.k, cfg.d_model, cfg.d_expert, 2)
+    ws = torch.empty(need + 512, dtype=torch.uint8, device="cuda")
+    fwd = lambda wsp, nbytes, T=cfg.T: lib.smoe_mlp_fwd(cx, stream, 1, cfg.act, X.data_ptr(), T, cfg.d_model, cfg.d_expert,
+                                                        W1.data_ptr(), W2.data_ptr(), ctypes.byref(rc_), cfg.k, gg.data_ptr(),
+                                                        Y.data_ptr(), Hpre.data_ptr(), H.data_ptr(), None, wsp, nbytes)
+    assert fwd(ws.data_ptr(), need - 256) == -3              # too small
+    assert fwd(ws.data_ptr() + 16, need) == -3               # misaligned
+    assert fwd(None, need) == -3
+    assert fwd(ws.data_ptr(), need, T=cfg.T - 1) == -1       # T * k does not match the routing
+    dX, dW1, dW2 = mark(cfg.T, cfg.d_model), mark(*W1.shape), mark(*W2.shape)
+    dg = torch.full((cfg.T, cfg.k), 7.0, device="cuda")
+    needb = lib.smoe_mlp_bwd_workspace_bytes(1, cfg.act, cfg.T, cfg.k, cfg.d_model, cfg.d_expert)
+    wsb = torch.empty(needb, dtype=torch.uint8, device="cuda")
+    bwd = lambda nbytes: lib.smoe_mlp_bwd(cx, stream, 1, cfg.act, dY.data_ptr(), X.data_ptr(), cfg.T, cfg.d_model, cfg.d_expert,
+                                          W1.data_ptr(), W2.data_ptr(), ctypes.byref(rc_), cfg.k, gg.data_ptr(), Hpre.data_ptr(),
+                                          H.data_ptr(), None, dX.data_ptr(), dW1.data_ptr(), dW2.data_ptr(), dg.data_ptr(),
+                                          wsb.data_ptr(), nbytes)
+    assert bwd(needb - 256) == -3
+    # routing: more experts than the per-expert counters in LDS allow
+    E_big = 20000
+    se = torch.full((64,), -7, dtype=torch.int32, device="cuda")
+    off = torch.full((E_big + 1,), -7, dtype=torch.int32, device="cuda")
+    eib = torch.zeros(32, 2, dtype=torch.int32, device="cuda")
+    wsr = torch.empty(max(lib.smoe_route_workspace_bytes(32, 2, E_big), 256), dtype=torch.uint8, device="cuda")
+    assert lib.smoe_route(cx, stream, eib.data_ptr(), 32, 2, E_big, se.data_ptr(), se.data_ptr(), off.data_ptr(), wsr.data_ptr(),
+                          wsr.numel()) == -2
+    assert lib.smoe_route_noalloc(cx, stream, eib.data_ptr(), 32, 2, E_big, se.data_ptr(), se.data_ptr(), off.data_ptr()) == -2
+    torch.cuda.synchronize()
+    for t in (Y, Hpre, H, dX, dW1, dW2, dg):
+        assert bool((t == 7.0).all()), "a refused call wrote to an output"
+    assert bool((se == -7).all()) and bool((off == -7).all())
+    # the same calls with valid arguments go through
+    assert fwd(ws.data_ptr(), need) == 0 and bwd(needb) == 0
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(Y.float()).all()) and not bool((dW1 == 7.0).all())
 
 
 def test_error_codes(smoe):
