@@ -310,6 +310,8 @@ def main():
     ap.add_argument("--kernel-reps", type=int, default=20)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB elementwise copy kernel (reference for the HBM byte counters)")
+    ap.add_argument("--tile-group", type=int, default=0,
+                    help="M-tiles per group of the persistent kernels' tile order (measurement aid; default: the library's 4)")
     ap.add_argument("--sweep", choices=["granularity", "sparsity"], default=None,
                     help="run the Sec. 4.2 granularity sweep or the Sec. 4.3 sparsity sweep instead of one workload "
                          "(one JSON line with all points)")
@@ -329,6 +331,9 @@ def main():
 
     cfg = si.CONFIGS[args.workload]
     td = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    if args.tile_group:
+        torch.cuda.set_device(0)
+        smoe.set_tile_group(args.tile_group)
     case = si.mlp_case(cfg, args.seed)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)

@@ -87,6 +87,12 @@ int smoe_abi_version(void);
  * context may be in progress. */
 int smoe_set_kernel_mode(smoe_ctx *ctx, int mode);
 
+/* Measurement aid.  The persistent scatter2scatter kernels number their output tiles in groups of group_m M-tiles x all
+ * N-tiles, and the 32 compute units of an XCD take 32 consecutive numbers, i.e. a group_m x (32 / group_m) patch of tiles
+ * that shares operand panels in that XCD's L2.  The default, 4, is the measured optimum (profiles/); 1 <= group_m <= 64.
+ * Results do not depend on it.  Host-only; writes the context, so no other call on it may be in progress. */
+int smoe_set_tile_group(smoe_ctx *ctx, int group_m);
+
 /* Measurement aid.  With a device array of 512 uint64 set, every launch of the persistent scatter2scatter
  * kernels (the products of smoe_plinear_fwd / _bwd, smoe_plinear_act_fwd, smoe_mlp_fwd / _bwd) makes block b
  * store, when it ends, the shader-clock cycles and the ticks of the constant 100 MHz counter between its first

@@ -20,7 +20,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libsmoe.so")
 
 EXPORTS = [
-    "smoe_create", "smoe_destroy", "smoe_strerror", "smoe_abi_version", "smoe_set_kernel_mode", "smoe_set_clock_probe",
+    "smoe_create", "smoe_destroy", "smoe_strerror", "smoe_abi_version", "smoe_set_kernel_mode", "smoe_set_clock_probe", "smoe_set_tile_group",
     "smoe_topk_gate", "smoe_topk_gate_bwd", "smoe_route_workspace_bytes", "smoe_route", "smoe_route_noalloc",
     "smoe_plinear_fwd", "smoe_plinear_bwd_workspace_bytes", "smoe_plinear_bwd",
     "smoe_plinear_act_fwd_workspace_bytes", "smoe_plinear_act_fwd", "smoe_mlp_fwd_workspace_bytes", "smoe_mlp_fwd", "smoe_mlp_saves_yhat", "smoe_mlp_bwd_workspace_bytes", "smoe_mlp_bwd",
@@ -55,6 +55,7 @@ lib.smoe_strerror.argtypes = [_i]
 lib.smoe_strerror.restype = ctypes.c_char_p
 lib.smoe_set_kernel_mode.argtypes = [_vp, _i]
 lib.smoe_set_clock_probe.argtypes = [_vp, _vp]
+lib.smoe_set_tile_group.argtypes = [_vp, _i]
 lib.smoe_topk_gate.argtypes = [_vp, _vp, _vp, _i, _i, _i, _vp, _vp]
 lib.smoe_topk_gate_bwd.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _vp]
 lib.smoe_attention_fwd.argtypes = [_vp, _vp, _i, _vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp]
@@ -116,6 +117,10 @@ def ctx(device: int | None = None) -> ctypes.c_void_p:
 
 def set_kernel_mode(mode: int):
     _check(lib.smoe_set_kernel_mode(ctx(), mode), "smoe_set_kernel_mode")
+
+
+def set_tile_group(group_m: int):
+    _check(lib.smoe_set_tile_group(ctx(), group_m), "smoe_set_tile_group")
 
 
 def set_clock_probe(buf: torch.Tensor | None):

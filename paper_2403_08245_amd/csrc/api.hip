@@ -17,6 +17,7 @@ bool dtype_ok(int dt) { return dt == SMOE_F32 || dt == SMOE_BF16; }
 
 int run_s2s(smoe_ctx *ctx, hipStream_t s, smoe_dtype dt, S2SArgs a) {
   a.grid = ctx->stream_grid;
+  a.group_m = ctx->group_m;
   a.clock_probe = ctx->clock_probe;
   if (dt == SMOE_BF16 && ctx->kernel_mode == 0 && s2s_decode_supported(a)) return launch_s2s_decode(s, a);
   if (dt == SMOE_BF16 && ctx->kernel_mode == 0 && s2s_stream_supported(a)) return launch_s2s_stream(s, a);
@@ -80,6 +81,7 @@ int smoe_create(smoe_ctx **out, int device) {
   // persistent kernels: one block per compute unit, dealt to the XCDs in eight equal shares
   c->stream_grid = c->num_cu >= 256 ? 256 : (c->num_cu & ~7);
   c->kernel_mode = 0;
+  c->group_m = 4;
   c->clock_probe = nullptr;
   c->route_scratch = nullptr;
   // kernel attributes and the address of a __device__ array are per device: set them with this context's device current, then restore the caller's
@@ -104,6 +106,12 @@ void smoe_destroy(smoe_ctx *ctx) { delete ctx; }
 int smoe_set_kernel_mode(smoe_ctx *ctx, int mode) {
   if (!ctx || mode < 0 || mode > 2) return SMOE_ERR_INVALID_ARG;
   ctx->kernel_mode = mode;
+  return SMOE_OK;
+}
+
+int smoe_set_tile_group(smoe_ctx *ctx, int group_m) {
+  if (!ctx || group_m < 1 || group_m > 64) return SMOE_ERR_INVALID_ARG;
+  ctx->group_m = group_m;
   return SMOE_OK;
 }
 
@@ -333,6 +341,7 @@ static int hidden_forward(smoe_ctx *ctx, hipStream_t s, smoe_dtype dtype, smoe_a
   S2SArgs fused = a1;
   fused.H = H;
   fused.grid = ctx->stream_grid;
+  fused.group_m = ctx->group_m;
   fused.clock_probe = ctx->clock_probe;
   if (act == SMOE_ACT_SWIGLU && dtype == SMOE_BF16 && ctx->kernel_mode == 0 &&
       (s2s_decode_supported(fused) || s2s_stream_swiglu_supported(fused))) {
@@ -540,6 +549,7 @@ int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
     x2.row_scale = gsorted;
     x2.dp_part = dp_part;
     x2.grid = ctx->stream_grid;
+    x2.group_m = ctx->group_m;
     x2.clock_probe = ctx->clock_probe;
     rc = launch_s2s_stream(s, x2);
     if (rc != SMOE_OK) return rc;

@@ -12,6 +12,7 @@ struct smoe_ctx {
   int num_cu;
   int stream_grid;  // blocks of the persistent kernels: one per compute unit, a multiple of 8 (one share per XCD), at most 256
   unsigned long long *clock_probe;  // device array the persistent s2s kernels report their clocks to, or NULL (smoe_set_clock_probe)
+  int group_m;      // M-tiles per group of the persistent scatter2scatter kernels' tile order (4; smoe_set_tile_group)
   int kernel_mode;  // 0 auto, 1 plain tiled kernels only, 2 one block per tile (testing aid, see smoe_set_kernel_mode)
   int32_t *route_scratch;  // this device's copy of the routing kernels' static scratch array (smoe_route_noalloc)
 };
@@ -98,6 +99,7 @@ struct S2SArgs {      // C[out(i), :] = A[in(i), :] * op(W[e(i)])   for sorted r
   // compute units that would otherwise idle (S2S_TAIL_WS_BYTES of device memory, or NULL: no split).
   float *tail_ws;
   int grid = 256;     // blocks of the persistent kernel (smoe_ctx::stream_grid)
+  int group_m = 4;    // tiles are numbered in groups of this many M-tiles x all N-tiles (smoe_ctx::group_m)
   // Optional fused SwiGLU of Alg. 3 (forward, expert-sorted output only): W's columns are
   // [gate | up] halves of width N / 2 and H [*, N / 2] receives silu(gate) * up; C may then be
   // NULL when the pre-activation is not kept.

@@ -1026,7 +1026,7 @@ template <bool TRANS_W, bool SCATTER_OUT, int ACT = 0> int launch_s2s_stream_cfg
 template <bool TRANS_W, bool SCATTER_OUT, int ACT, bool STATIC4> int launch_s2s_stream_one(hipStream_t s, const S2SArgs &a) {
   int tiles_n = (ACT == 1 || ACT == 2) ? ceil_div(a.N / 2, TB / 2) : ceil_div(a.N, TB);
   long long tiles_m = ceil_div(a.Tk, TB) + a.E;     // upper bound on sum_e ceil(n_e / 256)
-  int group_m = 4;
+  const int group_m = a.group_m;
   if (tiles_m * tiles_n > 0x7fffffffLL) return SMOE_ERR_UNSUPPORTED;
   S2SArgs args = a;
   int chunk;
@@ -1072,7 +1072,7 @@ bool s2s_stream_supported(const S2SArgs &a) {
   // sorted A, from the start of an expert's matrix) must fit the 32-bit offset of the loads
   long long a_rows = a.a_map.o ? (long long)a.Tk / fan + 1 : TB;
   long long w_rows = a.trans_w ? a.N : a.K;
-  return a.grid >= 8 && a.grid % 8 == 0 && a.grid <= MAX_STREAM_GRID && a.K % HK == 0 && a.K >= 3 * HK && a.N % 8 == 0 && a.ldw % 8 == 0 && a.Tk > 0 && a.E <= MAX_E &&
+  return a.grid >= 8 && a.grid % 8 == 0 && a.grid <= MAX_STREAM_GRID && a.group_m >= 1 && a.K % HK == 0 && a.K >= 3 * HK && a.N % 8 == 0 && a.ldw % 8 == 0 && a.Tk > 0 && a.E <= MAX_E &&
          (long long)a.Tk * fan < 0x100000000LL && a_rows * a.K * 2 < 0x100000000LL &&
          (w_rows + HK) * a.ldw * 2 < 0x100000000LL;
 }

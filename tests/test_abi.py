@@ -112,7 +112,7 @@ def test_every_entry_point_rejects_a_null_context_without_touching_the_gpu():
     import paper_2403_08245_amd as m
     lib = m.lib
     calls = {
-        "smoe_set_kernel_mode": (None, 0), "smoe_set_clock_probe": (None, None),
+        "smoe_set_kernel_mode": (None, 0), "smoe_set_clock_probe": (None, None), "smoe_set_tile_group": (None, 4),
         "smoe_topk_gate": (None, None, None, 4, 4, 2, None, None),
         "smoe_topk_gate_bwd": (None, None, None, None, None, 4, 4, 2, None),
         "smoe_route": (None, None, None, 4, 2, 4, None, None, None, None, 0),
