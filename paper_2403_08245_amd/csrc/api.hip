@@ -432,11 +432,13 @@ int smoe_mlp_fwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
 // Workspace of the backward pass: dYbar [Tk,d_model] (later reused for dXbar), dH [Tk,d_expert],
 // dHpre [Tk,d_h].
 // Backward passes that form dp in the epilogue of the W2^T product (bf16 through the persistent kernels).
-//   mode 1 (SwiGLU): the activation's derivative is applied there too; scratch = the unweighted and the weighted
-//     expert-sorted copies of dY [Tk,d_model] each (the first one later holds Xbar, then dXbar), dHpre [Tk,d_h].
-//   mode 2 (other activations): dp from the saved H; scratch = the unweighted sorted dY, then either the weighted copy or,
-//     when d_expert < d_model makes it the smaller tensor, the routing-weighted hidden rows Hw [Tk,d_expert] that let
-//     groupXTY form dW2 from the unweighted copy; dH [Tk,d_expert]; dHpre [Tk,d_h].
+// That product gathers the rows of dY itself; the one expert-sorted copy of dY [Tk,d_model] is for groupXTY (its array later
+// holds Xbar, then dXbar).
+//   mode 1 (SwiGLU): the activation's derivative is applied there too; scratch = the routing-weighted sorted copy of dY,
+//     dHpre [Tk,d_h].
+//   mode 2 (other activations): dp from the saved H; scratch = the weighted sorted copy of dY or, when d_expert < d_model
+//     makes them the smaller tensor, the plain sorted copy plus the routing-weighted hidden rows Hw [Tk,d_expert] that let
+//     groupXTY form dW2 from the plain copy; dH [Tk,d_expert]; dHpre [Tk,d_h].
 //   both: the sorted routing weights [Tk] and the slabs of dp [Tk, 2 * ceil(d_expert / 256)] fp32.
 struct MlpBwdEpiLayout {
   size_t dybar_u, second, dh, dhpre, gsorted, dp_part, total;
@@ -448,7 +450,7 @@ static MlpBwdEpiLayout mlp_bwd_epi_layout(int mode, size_t es, size_t Tk, int d_
   size_t off = 0;
   L.part_ld = 2 * ceil_div(d_expert, 256);
   L.use_hw = mode == 2 && d_expert < d_model;
-  L.dybar_u = off;  off += align256(Tk * d_model * es);
+  L.dybar_u = off;  off += L.use_hw ? align256(Tk * d_model * es) : 0;
   L.second = off;   off += align256(Tk * (size_t)(L.use_hw ? d_expert : d_model) * es);
   L.dh = off;       off += mode == 2 ? align256(Tk * (size_t)d_expert * es) : 0;
   L.dhpre = off;    off += align256(Tk * (size_t)d_h * es);
@@ -470,11 +472,11 @@ size_t smoe_mlp_bwd_workspace_bytes(smoe_dtype dtype, smoe_act act, int T, int k
 
 // How the backward pass of this shape runs: 0 = Alg. 2 step by step (dp from the forward's saved Yhat), 1 / 2 = dp in the
 // epilogue of the W2^T product as described above (the forward's unweighted Yhat is then not needed).
-static int mlp_bwd_mode(const smoe_ctx *ctx, smoe_dtype dtype, smoe_act act, int Tk, int E, int d_model, int d_expert) {
+static int mlp_bwd_mode(const smoe_ctx *ctx, smoe_dtype dtype, smoe_act act, int Tk, int k, int E, int d_model, int d_expert) {
   if (dtype != SMOE_BF16 || ctx->kernel_mode != 0 || Tk < 1) return 0;
   S2SArgs x;
   x.A = x.W = nullptr;  x.C = nullptr;
-  x.a_map = RowMap{nullptr, 1};  x.c_map = RowMap{nullptr, 1};
+  x.a_map = RowMap{(const int32_t *)1, k};  x.c_map = RowMap{nullptr, 1};   // the product gathers the rows of dY [T, d_model]
   x.offsets = nullptr;  x.E = E;  x.Tk = Tk;
   x.K = d_model;  x.N = d_expert;  x.ldw = d_model;  x.w_stride = (size_t)d_expert * d_model;  x.trans_w = 1;
   x.tail_ws = nullptr;  x.H = nullptr;
@@ -490,7 +492,7 @@ static int mlp_bwd_mode(const smoe_ctx *ctx, smoe_dtype dtype, smoe_act act, int
 
 int smoe_mlp_saves_yhat(smoe_ctx *ctx, smoe_dtype dtype, smoe_act act, int T, int k, int E, int d_model, int d_expert) {
   if (!ctx || !dtype_ok(dtype) || T < 0 || k < 1 || E < 1 || d_model < 1 || d_expert < 1) return SMOE_ERR_INVALID_ARG;
-  return mlp_bwd_mode(ctx, dtype, act, T * k, E, d_model, d_expert) ? 0 : 1;
+  return mlp_bwd_mode(ctx, dtype, act, T * k, k, E, d_model, d_expert) ? 0 : 1;
 }
 
 int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, const void *dY, const void *X, int T,
@@ -516,7 +518,7 @@ int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
     DWArgs z2{nullptr, nullptr, dW2, r->expert_offsets, r->E, 0, d_expert, d_model};
     return launch_dw_plain(s, dtype, z2);
   }
-  const int mode = mlp_bwd_mode(ctx, dtype, act, Tk, r->E, d_model, d_expert);
+  const int mode = mlp_bwd_mode(ctx, dtype, act, Tk, k, r->E, d_model, d_expert);
   if (!dY || !X || !W1 || !W2 || !gates || !saved_Hpre || !saved_H || (!saved_Yhat && !mode) || !dX || !dgates)
     return SMOE_ERR_INVALID_ARG;
   if (!aligned16(dY) || !aligned16(X) || !aligned16(W1) || !aligned16(W2) || !aligned16(saved_Hpre) ||
@@ -531,15 +533,13 @@ int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
     void *dYu = base + L.dybar_u, *second = base + L.second, *dH = base + L.dh, *dHpre = base + L.dhpre;
     float *gsorted = (float *)(base + L.gsorted), *dp_part = (float *)(base + L.dp_part);
     float *tail_ws = (float *)(base + L.total - S2S_TAIL_WS_BYTES);
-    if (L.use_hw) {      // one sorted copy of dY; the routing weights go into Hw instead
-      rc = launch_group(s, dtype, dY, r->sorted_scattered_idxs, k, nullptr, dYu, Tk, d_model);
-      if (rc != SMOE_OK) return rc;
-      rc = launch_sorted_weights(s, r->sorted_scattered_idxs, gates, gsorted, Tk);
-    } else {             // plain and weighted sorted copies in one pass (groupXTY for dW2 takes the weighted one)
-      rc = launch_group_pair(s, dtype, dY, r->sorted_scattered_idxs, k, gates, dYu, second, gsorted, Tk, d_model);
-    }
+    // The W2^T product gathers the rows of dY itself (Alg. 1's scattered input, fan-out k); groupXTY needs sorted rows, so
+    // one sorted copy is made for it: the routing-weighted one, or the plain one when the weights go into Hw instead.
+    rc = launch_group(s, dtype, dY, r->sorted_scattered_idxs, k, L.use_hw ? nullptr : gates, L.use_hw ? dYu : second, Tk, d_model);
     if (rc != SMOE_OK) return rc;
-    S2SArgs x2 = make_s2s(dYu, W2, mode == 1 ? dHpre : dH, r, d_expert, d_model, true, true, 1, true);
+    rc = launch_sorted_weights(s, r->sorted_scattered_idxs, gates, gsorted, Tk);
+    if (rc != SMOE_OK) return rc;
+    S2SArgs x2 = make_s2s(dY, W2, mode == 1 ? dHpre : dH, r, d_expert, d_model, true, false, k, true);
     if (mode == 1) {
       x2.Hpre_in = saved_Hpre;           // dHpre = sigma'(Hpre) p (dYu W2^T) straight from the accumulators
     } else {
@@ -564,7 +564,7 @@ int smoe_mlp_bwd(smoe_ctx *ctx, void *stream, smoe_dtype dtype, smoe_act act, co
     w2.split_ws = tail_ws;
     rc = run_dw(ctx, s, dtype, w2);
     if (rc != SMOE_OK) return rc;
-    void *Xbar = dYu;                                    // dYu is dead: its array holds Xbar, then dXbar
+    void *Xbar = L.use_hw ? dYu : second;                // the sorted copy of dY is dead: its array holds Xbar, then dXbar
     rc = launch_group(s, dtype, X, r->sorted_scattered_idxs, k, nullptr, Xbar, Tk, d_model);
     if (rc != SMOE_OK) return rc;
     DWArgs w1{Xbar, dHpre, dW1, r->expert_offsets, r->E, Tk, d_model, d_h};

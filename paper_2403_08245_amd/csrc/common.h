@@ -71,10 +71,6 @@ int launch_act_bwd(hipStream_t s, smoe_dtype dt, smoe_act act, const void *Hpre,
 int launch_combine(hipStream_t s, smoe_dtype dt, const void *Yhat, const float *g, void *Y, int T, int k, int d);
 int launch_group(hipStream_t s, smoe_dtype dt, const void *in, const int32_t *o, int fan, const float *g,
                  void *out, int Tk, int d);
-// One pass over `in` for Alg. 2's weight-and-group step when both forms are needed: out_plain[i] = in[o[i] / fan],
-// out_weighted[i] = g[o[i]] * in[o[i] / fan], g_sorted[i] = g[o[i]].
-int launch_group_pair(hipStream_t s, smoe_dtype dt, const void *in, const int32_t *o, int fan, const float *g,
-                      void *out_plain, void *out_weighted, float *g_sorted, int Tk, int d);
 // dg[o[i]] = sum_c part[i, c] (c ascending): finishes the routing-weight gradient left in slabs by the fused
 // SwiGLU backward epilogue.
 int launch_dp_reduce(hipStream_t s, const float *part, int ld, const int32_t *o, float *dg, int Tk);
@@ -105,8 +101,8 @@ struct S2SArgs {      // C[out(i), :] = A[in(i), :] * op(W[e(i)])   for sorted r
   // NULL when the pre-activation is not kept.
   void *H;
   // Optional fused SwiGLU backward of Alg. 3 (input-gradient product of the second ParallelLinear, expert-sorted
-  // in and out, op(W) = W^T, N = d_expert): A holds the UNWEIGHTED expert-sorted upstream rows, so the fp32
-  // accumulators are dH / p.  With Hpre_in [Tk, 2N] (the saved pre-activation), row_scale [Tk] (the routing
+  // out, op(W) = W^T, N = d_expert): A holds the UNWEIGHTED upstream rows (gathered through a_map or already
+  // expert-sorted), so the fp32 accumulators are dH / p.  With Hpre_in [Tk, 2N] (the saved pre-activation), row_scale [Tk] (the routing
   // weight of every sorted row) and dp_part [Tk, 2 * ceil(N / 256)] fp32 set, the epilogue writes
   // C = dHpre [Tk, 2N] = sigma'(Hpre) * row_scale * acc instead of dH, and per row and 128-column slab the
   // partial dot <acc, silu(gate) * up> whose sum over the slabs is Alg. 2's dp for that row.
@@ -116,7 +112,7 @@ struct S2SArgs {      // C[out(i), :] = A[in(i), :] * op(W[e(i)])   for sorted r
   const void *Hpre_in = nullptr;
   const float *row_scale = nullptr;
   float *dp_part = nullptr;
-  // The same idea for any activation (still the W2^T product on unweighted sorted rows): with H_in [Tk, N] (the saved
+  // The same idea for any activation (still the W2^T product on unweighted rows): with H_in [Tk, N] (the saved
   // hidden activations), row_scale and dp_part set and Hpre_in NULL, the epilogue writes C = dH = row_scale * acc, the
   // slabs of dp = <acc, H>, and, when Hw_out [Tk, N] is given, Hw = row_scale * H (the routing-weighted hidden rows
   // that let groupXTY take the unweighted sorted dY for dW2 as well).  The activation's derivative stays a row kernel.

@@ -135,30 +135,6 @@ __global__ void __launch_bounds__(256) group_kernel(const T *__restrict__ in, co
   }
 }
 
-// ---- group, both forms in one pass: plain and routing-weighted copies of the sorted rows, and the sorted weights
-template <typename T>
-__global__ void __launch_bounds__(256) group_pair_kernel(const T *__restrict__ in, const int32_t *__restrict__ o, int fan,
-                                                         const float *__restrict__ g, T *__restrict__ out_plain,
-                                                         T *__restrict__ out_weighted, float *__restrict__ g_sorted,
-                                                         size_t Tk, int d) {
-  constexpr int V = 16 / sizeof(T);
-  const size_t per_row = d / V;
-  const size_t total = Tk * per_row;
-  for (size_t w = blockIdx.x * (size_t)blockDim.x + threadIdx.x; w < total; w += (size_t)gridDim.x * blockDim.x) {
-    size_t i = w / per_row;
-    int c = (int)(w % per_row) * V;
-    int s = o[i];
-    float a[V];
-    load_vec<T>(in + (size_t)(s / fan) * d + c, a);
-    store_vec<T>(out_plain + i * d + c, a);
-    const float gs = g[s];
-    if (c == 0) g_sorted[i] = gs;
-#pragma unroll
-    for (int q = 0; q < V; ++q) a[q] *= gs;
-    store_vec<T>(out_weighted + i * d + c, a);
-  }
-}
-
 // ---- dg[o[i]] = sum_c part[i, c], c ascending (fixed order): one thread per sorted row
 __global__ void __launch_bounds__(256) dp_reduce_kernel(const float *__restrict__ part, int ld, const int32_t *__restrict__ o,
                                                         float *__restrict__ dg, int Tk) {
@@ -261,23 +237,6 @@ static int group_t(hipStream_t s, const void *in, const int32_t *o, int fan, con
 }
 int launch_group(hipStream_t s, smoe_dtype dt, const void *in, const int32_t *o, int fan, const float *g, void *out, int Tk, int d) {
   return dt == SMOE_BF16 ? group_t<bf16_t>(s, in, o, fan, g, out, Tk, d) : group_t<float>(s, in, o, fan, g, out, Tk, d);
-}
-
-template <typename T>
-static int group_pair_t(hipStream_t s, const void *in, const int32_t *o, int fan, const float *g, void *out_plain,
-                        void *out_weighted, float *g_sorted, int Tk, int d) {
-  if (!vec_ok<T>(d)) return SMOE_ERR_UNSUPPORTED;
-  size_t items = (size_t)Tk * (d / (16 / sizeof(T)));
-  if (!items) return SMOE_OK;
-  hipLaunchKernelGGL((group_pair_kernel<T>), dim3(grid_for(items)), dim3(256), 0, s, (const T *)in, o, fan, g, (T *)out_plain,
-                     (T *)out_weighted, g_sorted, (size_t)Tk, d);
-  SMOE_LAUNCH_CHECK();
-  return SMOE_OK;
-}
-int launch_group_pair(hipStream_t s, smoe_dtype dt, const void *in, const int32_t *o, int fan, const float *g, void *out_plain,
-                      void *out_weighted, float *g_sorted, int Tk, int d) {
-  return dt == SMOE_BF16 ? group_pair_t<bf16_t>(s, in, o, fan, g, out_plain, out_weighted, g_sorted, Tk, d)
-                         : group_pair_t<float>(s, in, o, fan, g, out_plain, out_weighted, g_sorted, Tk, d);
 }
 
 __global__ void __launch_bounds__(256) sorted_weights_kernel(const int32_t *__restrict__ o, const float *__restrict__ g,

@@ -1078,13 +1078,11 @@ bool s2s_stream_supported(const S2SArgs &a) {
 }
 
 bool s2s_stream_swiglu_bwd_supported(const S2SArgs &a) {
-  return s2s_stream_supported(a) && a.trans_w && !a.c_map.o && !a.a_map.o && a.Hpre_in && a.row_scale && a.dp_part &&
-         a.N % 8 == 0;
+  return s2s_stream_supported(a) && a.trans_w && !a.c_map.o && a.Hpre_in && a.row_scale && a.dp_part && a.N % 8 == 0;
 }
 
 bool s2s_stream_dp_supported(const S2SArgs &a) {
-  return s2s_stream_supported(a) && a.trans_w && !a.c_map.o && !a.a_map.o && a.H_in && !a.Hpre_in && a.row_scale && a.dp_part &&
-         a.N % 8 == 0;
+  return s2s_stream_supported(a) && a.trans_w && !a.c_map.o && a.H_in && !a.Hpre_in && a.row_scale && a.dp_part && a.N % 8 == 0;
 }
 
 bool s2s_stream_swiglu_supported(const S2SArgs &a) {

@@ -54,15 +54,16 @@ def test_workspace_queries_are_pure_host_arithmetic():
     assert lib.smoe_mlp_fwd_workspace_bytes(BF16, SWIGLU, T, k, d_model, d_expert, 1) == 64 * MiB
     inf = lib.smoe_mlp_fwd_workspace_bytes(BF16, SWIGLU, T, k, d_model, d_expert, 0)
     assert inf == 64 * MiB + 2 * Tk * (2 * d_expert + d_expert + d_model)
-    # bf16 backward with the routing-weight gradient formed in a product's epilogue: two sorted copies of dY (or one plus
-    # the weighted hidden rows when those are narrower), dH, dHpre, the sorted weights and the fp32 slabs of dp
+    # bf16 backward with the routing-weight gradient formed in a product's epilogue: one sorted copy of dY (the product
+    # gathers its rows itself; plus the weighted hidden rows when those are the narrower tensor), dH, dHpre, the sorted
+    # weights and the fp32 slabs of dp
     bwd = lib.smoe_mlp_bwd_workspace_bytes(BF16, GELU, T, k, d_model, d_expert)
-    assert bwd == 64 * MiB + 2 * Tk * (2 * d_model + d_expert + d_expert) + 4 * Tk + 4 * Tk * 2 * 3
+    plain = 2 * Tk * (d_model + d_expert + d_expert)     # (the step-by-step layout dYbar, dH, dHpre: whichever is larger)
+    assert bwd == 64 * MiB + max(2 * Tk * (d_model + d_expert + d_expert) + 4 * Tk + 4 * Tk * 2 * 3, plain)
     narrow = lib.smoe_mlp_bwd_workspace_bytes(BF16, GELU, T, k, d_model, 256)
     assert narrow == 64 * MiB + 2 * Tk * (d_model + 256 + 256 + 256) + 4 * Tk + 4 * Tk * 2 * 1
     swi = lib.smoe_mlp_bwd_workspace_bytes(BF16, SWIGLU, T, k, d_model, d_expert)
-    # (the query covers whichever path a shape takes: here the step-by-step layout dYbar, dH, dHpre is the larger one)
-    assert swi == 64 * MiB + max(2 * Tk * (2 * d_model + 2 * d_expert) + 4 * Tk + 4 * Tk * 2 * 3, 2 * Tk * (d_model + 3 * d_expert))
+    assert swi == 64 * MiB + max(2 * Tk * (d_model + 2 * d_expert) + 4 * Tk + 4 * Tk * 2 * 3, 2 * Tk * (d_model + 3 * d_expert))
     assert lib.smoe_mlp_bwd_workspace_bytes(F32, GELU, T, k, d_model, d_expert) == 64 * MiB + 4 * Tk * (d_model + 2 * d_expert)
     # ParallelLinear backward: a grouped copy of dY and of X only for the side that arrives scattered
     both = lib.smoe_plinear_bwd_workspace_bytes(BF16, T, d_model, d_expert, Tk, k, 0, 0, 0)

@@ -174,14 +174,14 @@ def test_fused_swiglu_forward_every_row_over_several_rounds(smoe, d_model, d_exp
 
 @pytest.mark.parametrize("act,T,d_model,d_expert", [
     pytest.param(si.ACT_SWIGLU, 4096, 128, 4096, id="swiglu-derivative-in-epilogue"),
-    pytest.param(si.ACT_GELU, 4096, 128, 4096, id="gelu-two-sorted-copies"),
+    pytest.param(si.ACT_GELU, 4096, 128, 4096, id="gelu-weighted-sorted-copy"),
     pytest.param(si.ACT_GELU, 16384, 1280, 1024, id="gelu-weighted-hidden-rows"),
     pytest.param(si.ACT_NONE, 4096, 160, 3848, id="identity-ragged-width"),
 ])
 def test_backward_with_dp_in_epilogue_over_several_rounds(smoe, act, T, d_model, d_expert):
     """The W2^T input-gradient product with the routing-weight gradient (and for SwiGLU the activation's derivative)
-    in its epilogue, 500+ tiles; for the other activations the two ways of forming dW2 (a weighted second sorted copy
-    of dY, or routing-weighted hidden rows when those are narrower).  The intermediate tensors are scratch; what they
+    in its epilogue, 500+ tiles; for the other activations the two ways of forming dW2 (from a routing-weighted sorted
+    copy of dY, or from a plain one and routing-weighted hidden rows when those are narrower).  The intermediate tensors are scratch; what they
     feed is compared: dgates and dX on tokens drawn from every tile of every expert, two column pairs of dW1 and two
     rows of dW2 from every 256-unit tile for every expert (each sums over all the expert's rows), and every output
     must be free of the poison the workspace and outputs start with.  The forward's unweighted second product is not
